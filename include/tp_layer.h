@@ -1,0 +1,172 @@
+/*
+ * tp_layer.h - C ABI of the tensor-parallel transformer-layer shard for MI355X (gfx950).
+ *
+ * One call computes what ONE tensor-parallel rank computes for ONE transformer layer under the
+ * speed-optimised distribution of the paper (arXiv 2111.05972, App. F.1 "Speed-optimized
+ * distribution"; Sec. 5.3): in the self-attention block and in the MLP block the first linear
+ * layer is split across ranks over its output channels and the second over its input channels.
+ * The activations between the two are sharded, everything else is replicated, and each block ends
+ * in a partial sum that the ranks of the tensor-parallel group would all-reduce.  This library
+ * stops before that all-reduce: partial sums are returned as they are (forward), and so are the
+ * partial input gradients that `bwd_allreduce_for_tp` (App. I.5) would reduce (backward).
+ *
+ * Notation: H hidden size, nh heads, dh head size, I MLP width, T tensor-parallel degree,
+ * r rank, S sequence length, B micro-batch, M = B*S tokens, nl = nh/T, Hl = nl*dh, Il = I/T.
+ *
+ * Layout.  Every tensor is dense row-major in DEVICE memory; a linear layer is y = x W + b with
+ * W stored [in, out].  Rank r holds
+ *   w_qkv [H, 3*Hl]  columns ordered (q | k | v), then local head, then dh;   b_qkv [3*Hl]
+ *   w_o   [Hl, H]    rows r*Hl .. of the unsharded matrix;                      b_o   [H]
+ *   w_up  [H, Il]    columns r*Il .. of the unsharded matrix;                   b_up  [Il]
+ *   w_dn  [Il, H]    rows r*Il .. of the unsharded matrix;                      b_dn  [H]
+ * Activations and their gradients are [M, H] (token m = b*S + s).  Element type is `dtype`
+ * (float, or bfloat16 with float accumulation) for everything except LSE and the softmax
+ * row terms, which are float.
+ *
+ * The bias of a row-split linear layer lives on one rank only ((W1 x1 + b) + W2 x2 = W x + b,
+ * caption of Fig. 7).  TPL_ROW_EPILOGUE marks that rank: it adds b_o / b_dn and the residual
+ * input to its partial sums, and in backward receives db_o, db_dn and adds dy to its partial dx.
+ *
+ * Ownership.  The caller owns every buffer, including `saved` and `ws`; the library allocates
+ * nothing, never synchronises, and enqueues all work on `hip_stream` (a hipStream_t passed as
+ * void*; NULL = the default stream).  Pointers must be 16-byte aligned.  Outputs must not alias
+ * inputs.  Gradients are overwritten, not accumulated.  `ws` contents need not be preserved
+ * between calls; calls that share a `ws` must be stream-ordered.
+ *
+ * Errors.  Every entry point returns a tpl_status and never aborts; arguments are validated
+ * before anything is enqueued.
+ */
+#ifndef TP_LAYER_H
+#define TP_LAYER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TPL_OK = 0,
+    TPL_EINVAL = 1,        /* NULL pointer, non-positive size, sizes that do not divide          */
+    TPL_EUNSUPPORTED = 2,  /* valid layer, but a shape/dtype this build has no kernel for       */
+    TPL_EWORKSPACE = 3,    /* ws_bytes smaller than tp_layer_workspace_bytes()                  */
+    TPL_EALIGN = 4,        /* a device pointer is not 16-byte aligned                           */
+    TPL_EHIP = 5           /* the HIP runtime refused a launch                                  */
+} tpl_status;
+
+typedef enum { TPL_F32 = 0, TPL_BF16 = 1 } tpl_dtype;
+
+enum {
+    TPL_CAUSAL = 1u,       /* query i attends keys j <= i (else no mask); Sec. I.4 `causal_mask_size` */
+    TPL_ROW_EPILOGUE = 2u  /* this rank adds b_o, b_dn and the residual (tp_rank 0 by the Fig. 7 rule) */
+};
+
+/* The layer and this rank's place in it (App. F.1; constructor arguments of
+ * DistributedTransformerLayer in Sec. I.4; tensor_parallel_degree in Sec. I.1). */
+typedef struct {
+    int32_t hidden;        /* H                                                    */
+    int32_t heads;         /* nh, over all ranks                                   */
+    int32_t head_dim;      /* dh; 0 means hidden / heads                           */
+    int32_t intermediate;  /* I, over all ranks; 0 means 4 * hidden                */
+    int32_t tp_degree;     /* T                                                    */
+    int32_t tp_rank;       /* r, 0 <= r < T (identifies the shard; not used in arithmetic) */
+    int32_t seq;           /* S                                                    */
+    int32_t micro_batch;   /* B                                                    */
+    int32_t dtype;         /* tpl_dtype                                            */
+    uint32_t flags;        /* TPL_CAUSAL | TPL_ROW_EPILOGUE                        */
+} tp_layer_desc;
+
+/* This rank's parameter shard (device pointers, read-only).  b_o and b_dn may be NULL unless
+ * TPL_ROW_EPILOGUE is set. */
+typedef struct {
+    const void *w_qkv, *b_qkv, *w_o, *b_o, *w_up, *b_up, *w_dn, *b_dn;
+} tp_layer_params;
+
+/* Gradients of the shard (device pointers, written).  db_o and db_dn are written only with
+ * TPL_ROW_EPILOGUE and may be NULL otherwise. */
+typedef struct {
+    void *dw_qkv, *db_qkv, *dw_o, *db_o, *dw_up, *db_up, *dw_dn, *db_dn;
+} tp_layer_grads;
+
+/* Byte offsets inside `saved` of what forward keeps for backward. */
+typedef struct {
+    size_t qkv;  /* [M, 3*Hl] dtype : fused projection output, columns (q|k|v, head, dh) */
+    size_t o;    /* [M, Hl]   dtype : attention output, columns (head, dh)                */
+    size_t lse;  /* [B, nl, S] float: log-sum-exp of each softmax row                    */
+    size_t u;    /* [M, Il]   dtype : MLP pre-activation                                 */
+    size_t g;    /* [M, Il]   dtype : gelu(u)                                            */
+    size_t total;
+} tp_layer_saved_layout;
+
+/* Pure host check of a descriptor: sizes positive, heads*head_dim == hidden, heads and
+ * intermediate divisible by tp_degree, 0 <= tp_rank < tp_degree, known dtype and flags.
+ * TPL_EUNSUPPORTED if the layer is valid but not computable here (bf16 needs H, Hl, Il
+ * multiples of 8 for 16-byte rows; head_dim <= 256).  Needs no GPU. */
+int tp_layer_validate(const tp_layer_desc* desc);
+
+/* Size and layout of the `saved` buffer.  Return 0 / TPL_EINVAL for an invalid descriptor. */
+size_t tp_layer_saved_bytes(const tp_layer_desc* desc);
+int tp_layer_saved_offsets(const tp_layer_desc* desc, tp_layer_saved_layout* out);
+
+/* Scratch the forward (bwd == 0) or backward (bwd != 0) pass needs; 0 for an invalid descriptor. */
+size_t tp_layer_workspace_bytes(const tp_layer_desc* desc, int bwd);
+
+/* Forward of the shard (App. F.1):
+ *   QKV = x_attn w_qkv + b_qkv;  per (b, local head): P = softmax(mask(Q K^T / sqrt(dh))), O = P V
+ *   y_attn_partial = O w_o            (+ b_o  + x_attn with TPL_ROW_EPILOGUE)
+ *   U = x_mlp w_up + b_up;  G = gelu(U) (exact erf form)
+ *   y_mlp_partial  = G w_dn           (+ b_dn + x_mlp  with TPL_ROW_EPILOGUE)
+ * x_attn, x_mlp: [M, H] inputs replicated over the tensor-parallel group (x_mlp would be the
+ * all-reduced, normalised attention output in a full model; the caller supplies it).
+ * y_*_partial: [M, H], the unreduced row-parallel partial sums.  `saved`: tp_layer_saved_bytes(). */
+int tp_layer_fwd(const tp_layer_desc* desc, const tp_layer_params* params,
+                 const void* x_attn, const void* x_mlp,
+                 void* y_attn_partial, void* y_mlp_partial,
+                 void* saved, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Backward of the shard for upstream gradients dy_attn, dy_mlp [M, H] (replicated):
+ *   dG = dy_mlp w_dn^T; dw_dn = G^T dy_mlp; dU = dG * gelu'(U); dw_up = x_mlp^T dU; db_up = sum_m dU
+ *   dx_mlp_partial = dU w_up^T        (+ dy_mlp with TPL_ROW_EPILOGUE; then also db_dn = sum_m dy_mlp)
+ *   dO = dy_attn w_o^T; dw_o = O^T dy_attn; softmax-attention backward gives dQKV
+ *   dw_qkv = x_attn^T dQKV; db_qkv = sum_m dQKV
+ *   dx_attn_partial = dQKV w_qkv^T    (+ dy_attn with TPL_ROW_EPILOGUE; then also db_o = sum_m dy_attn)
+ * `saved` is what tp_layer_fwd wrote for the same inputs. */
+int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* params,
+                 const void* x_attn, const void* x_mlp,
+                 const void* dy_attn, const void* dy_mlp,
+                 const void* saved, const tp_layer_grads* grads,
+                 void* dx_attn_partial, void* dx_mlp_partial,
+                 void* ws, size_t ws_bytes, void* hip_stream);
+
+/* One GEMM of the path with its fused epilogue, exposed for per-kernel tests and timing:
+ *   C[M,N] = epi( opA(A) opB(B) ),  element type `dtype`, float accumulation.
+ * trans_a == 0: A is [M,K] row-major, else A is [K,M] row-major (used as its transpose).
+ * trans_b == 0: B is [K,N] row-major, else B is [N,K] row-major (used as its transpose).
+ * epi: v = acc (+ bias[n] if bias) (+ resid[m,n] if resid);
+ *      TPL_EPI_GELU : aux[m,n] = v (pre-activation), C = gelu(v)
+ *      TPL_EPI_DGELU: C = v * gelu'(aux[m,n])
+ * bias, resid, aux may be NULL when unused.  ws as for tp_layer_fwd (tp_layer_gemm_workspace_bytes). */
+enum { TPL_EPI_NONE = 0, TPL_EPI_GELU = 1, TPL_EPI_DGELU = 2 };
+size_t tp_layer_gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K);
+int tp_layer_gemm(int dtype, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
+                  const void* A, const void* B, void* C,
+                  const void* bias, const void* resid, void* aux, int epi,
+                  void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Softmax attention over local heads, exposed for per-kernel tests and timing.
+ * qkv [B*S, 3*nl*dh] (columns q|k|v, head, dh) -> o [B*S, nl*dh], lse [B, nl, S] float. */
+int tp_layer_attn_fwd(int dtype, int B, int S, int nl, int dh, int causal,
+                      const void* qkv, void* o, float* lse, void* hip_stream);
+/* d_scratch: [B, nl, S] float scratch (row sums of dO*O); dqkv [B*S, 3*nl*dh]. */
+int tp_layer_attn_bwd(int dtype, int B, int S, int nl, int dh, int causal,
+                      const void* qkv, const void* o, const float* lse, const void* d_o,
+                      void* dqkv, float* d_scratch, void* hip_stream);
+
+/* Static description of a status code. */
+const char* tp_layer_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TP_LAYER_H */

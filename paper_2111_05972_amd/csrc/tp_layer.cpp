@@ -1,0 +1,326 @@
+// C-ABI entry points: descriptor validation, buffer layouts, and the order in which the kernels of
+// one tensor-parallel rank's forward and backward pass are enqueued (App. F.1 of the paper).
+#include "../../include/tp_layer.h"
+
+#include <algorithm>
+
+#include "kernels.h"
+
+using namespace tpl;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+// Resolved sizes of a valid descriptor.
+struct Dims {
+    int64_t H, nh, dh, I, T, r, S, B, M, nl, Hl, Il;
+    int dtype;
+    size_t esz;
+    bool causal, row_epi;
+};
+
+int resolve(const tp_layer_desc* d, Dims* o) {
+    if (!d) return TPL_EINVAL;
+    if (d->hidden <= 0 || d->heads <= 0 || d->tp_degree <= 0 || d->seq <= 0 || d->micro_batch <= 0)
+        return TPL_EINVAL;
+    if (d->head_dim < 0 || d->intermediate < 0) return TPL_EINVAL;
+    if (d->dtype != TPL_F32 && d->dtype != TPL_BF16) return TPL_EINVAL;
+    if (d->flags & ~(uint32_t)(TPL_CAUSAL | TPL_ROW_EPILOGUE)) return TPL_EINVAL;
+    if (d->tp_rank < 0 || d->tp_rank >= d->tp_degree) return TPL_EINVAL;
+    Dims x;
+    x.H = d->hidden; x.nh = d->heads; x.T = d->tp_degree; x.r = d->tp_rank;
+    x.S = d->seq; x.B = d->micro_batch;
+    if (x.H % x.nh) return TPL_EINVAL;
+    x.dh = d->head_dim ? d->head_dim : x.H / x.nh;
+    if (x.dh * x.nh != x.H) return TPL_EINVAL;
+    x.I = d->intermediate ? d->intermediate : 4 * x.H;
+    if (x.nh % x.T || x.I % x.T) return TPL_EINVAL;
+    x.M = x.B * x.S; x.nl = x.nh / x.T; x.Hl = x.nl * x.dh; x.Il = x.I / x.T;
+    x.dtype = d->dtype; x.esz = d->dtype == TPL_F32 ? 4 : 2;
+    x.causal = d->flags & TPL_CAUSAL; x.row_epi = d->flags & TPL_ROW_EPILOGUE;
+    if (x.M > (int64_t)1 << 24 || x.H > (int64_t)1 << 20 || x.I > (int64_t)1 << 24) return TPL_EUNSUPPORTED;
+    if (x.dh > 256) return TPL_EUNSUPPORTED;
+    // 16-byte rows for every matrix the kernels touch
+    if (x.dtype == TPL_BF16 && (x.H % 8 || x.Hl % 8 || x.Il % 8)) return TPL_EUNSUPPORTED;
+    if (x.dtype == TPL_F32 && (x.H % 4 || x.Hl % 4 || x.Il % 4)) return TPL_EUNSUPPORTED;
+    if (o) *o = x;
+    return TPL_OK;
+}
+
+void saved_layout(const Dims& x, tp_layer_saved_layout* L) {
+    size_t off = 0;
+    L->qkv = off; off += up((size_t)x.M * 3 * x.Hl * x.esz);
+    L->o = off;   off += up((size_t)x.M * x.Hl * x.esz);
+    L->lse = off; off += up((size_t)x.B * x.nl * x.S * sizeof(float));
+    L->u = off;   off += up((size_t)x.M * x.Il * x.esz);
+    L->g = off;   off += up((size_t)x.M * x.Il * x.esz);
+    L->total = off;
+}
+
+size_t gemm_ws(int dtype, int64_t M, int64_t N, int64_t K) {
+    return dtype == TPL_BF16 ? up(gemm_bf16_workspace_bytes(M, N, K)) : 0;
+}
+
+// Backward scratch: dU, dO, dQKV, D, column-sum partials, GEMM scratch.
+struct BwdWs { size_t du, d_o, dqkv, dsum, colsum, gemm, total; };
+
+size_t fwd_gemm_ws(const Dims& x) {
+    size_t g = 0;
+    g = std::max(g, gemm_ws(x.dtype, x.M, 3 * x.Hl, x.H));
+    g = std::max(g, gemm_ws(x.dtype, x.M, x.H, x.Hl));
+    g = std::max(g, gemm_ws(x.dtype, x.M, x.Il, x.H));
+    g = std::max(g, gemm_ws(x.dtype, x.M, x.H, x.Il));
+    return std::max(g, ALIGN);
+}
+
+void bwd_layout(const Dims& x, BwdWs* W) {
+    size_t off = 0;
+    W->du = off;   off += up((size_t)x.M * x.Il * x.esz);
+    W->d_o = off;  off += up((size_t)x.M * x.Hl * x.esz);
+    W->dqkv = off; off += up((size_t)x.M * 3 * x.Hl * x.esz);
+    W->dsum = off; off += up((size_t)x.B * x.nl * x.S * sizeof(float));
+    int64_t nmax = std::max(std::max(x.Il, 3 * x.Hl), x.H);
+    W->colsum = off; off += up(colsum_scratch_bytes(x.M, nmax));
+    size_t g = fwd_gemm_ws(x);   // dgrad shapes are the forward shapes with N and K swapped
+    g = std::max(g, gemm_ws(x.dtype, x.M, x.Hl, x.H));
+    g = std::max(g, gemm_ws(x.dtype, x.M, x.H, 3 * x.Hl));
+    g = std::max(g, gemm_ws(x.dtype, x.Il, x.H, x.M));
+    g = std::max(g, gemm_ws(x.dtype, x.H, x.Il, x.M));
+    g = std::max(g, gemm_ws(x.dtype, x.Hl, x.H, x.M));
+    g = std::max(g, gemm_ws(x.dtype, x.H, 3 * x.Hl, x.M));
+    W->gemm = off; off += g;
+    W->total = off;
+}
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+int run_gemm(GemmArgs& g) {
+    hipError_t e;
+    if (g.dtype == BF16 && gemm_bf16_supported(g)) e = gemm_bf16(g);
+    else e = gemm_simple(g);
+    return e == hipSuccess ? TPL_OK : TPL_EHIP;
+}
+
+int run_attn(AttnArgs& a, bool bwd) {
+    hipError_t e;
+    if (a.dtype == BF16 && attn_bf16_supported(a)) e = bwd ? attn_bf16_bwd(a) : attn_bf16_fwd(a);
+    else e = bwd ? attn_simple_bwd(a) : attn_simple_fwd(a);
+    return e == hipSuccess ? TPL_OK : TPL_EHIP;
+}
+
+GemmArgs mk(const Dims& x, int ta, int tb, int64_t M, int64_t N, int64_t K, const void* A,
+            const void* B, void* C, void* ws, size_t ws_bytes, hipStream_t s) {
+    GemmArgs g{};
+    g.dtype = x.dtype; g.trans_a = ta; g.trans_b = tb; g.M = M; g.N = N; g.K = K;
+    g.A = A; g.B = B; g.C = C; g.epi = EPI_NONE; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = s;
+    return g;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tp_layer_validate(const tp_layer_desc* desc) { return resolve(desc, nullptr); }
+
+size_t tp_layer_saved_bytes(const tp_layer_desc* desc) {
+    Dims x;
+    if (resolve(desc, &x) != TPL_OK) return 0;
+    tp_layer_saved_layout L;
+    saved_layout(x, &L);
+    return L.total;
+}
+
+int tp_layer_saved_offsets(const tp_layer_desc* desc, tp_layer_saved_layout* out) {
+    Dims x;
+    int rc = resolve(desc, &x);
+    if (rc != TPL_OK) return rc;
+    if (!out) return TPL_EINVAL;
+    saved_layout(x, out);
+    return TPL_OK;
+}
+
+size_t tp_layer_workspace_bytes(const tp_layer_desc* desc, int bwd) {
+    Dims x;
+    if (resolve(desc, &x) != TPL_OK) return 0;
+    if (!bwd) return fwd_gemm_ws(x);
+    BwdWs W;
+    bwd_layout(x, &W);
+    return W.total;
+}
+
+int tp_layer_fwd(const tp_layer_desc* desc, const tp_layer_params* p, const void* x_attn,
+                 const void* x_mlp, void* y_attn, void* y_mlp, void* saved, void* ws,
+                 size_t ws_bytes, void* hip_stream) {
+    Dims x;
+    int rc = resolve(desc, &x);
+    if (rc != TPL_OK) return rc;
+    if (!p || !x_attn || !x_mlp || !y_attn || !y_mlp || !saved || !ws) return TPL_EINVAL;
+    if (!p->w_qkv || !p->b_qkv || !p->w_o || !p->w_up || !p->b_up || !p->w_dn) return TPL_EINVAL;
+    if (x.row_epi && (!p->b_o || !p->b_dn)) return TPL_EINVAL;
+    const void* ptrs[] = {x_attn, x_mlp, y_attn, y_mlp, saved, ws, p->w_qkv, p->b_qkv, p->w_o,
+                          p->b_o, p->w_up, p->b_up, p->w_dn, p->b_dn};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    if (ws_bytes < fwd_gemm_ws(x)) return TPL_EWORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    tp_layer_saved_layout L;
+    saved_layout(x, &L);
+    char* sv = (char*)saved;
+    void *qkv = sv + L.qkv, *o = sv + L.o, *u = sv + L.u, *g = sv + L.g;
+    float* lse = (float*)(sv + L.lse);
+
+    // attention block: column-parallel fused QKV, attention on the local heads, row-parallel out-proj
+    GemmArgs g1 = mk(x, 0, 0, x.M, 3 * x.Hl, x.H, x_attn, p->w_qkv, qkv, ws, ws_bytes, s);
+    g1.bias = p->b_qkv;
+    if ((rc = run_gemm(g1))) return rc;
+    AttnArgs at{};
+    at.dtype = x.dtype; at.B = (int)x.B; at.S = (int)x.S; at.nl = (int)x.nl; at.dh = (int)x.dh;
+    at.causal = x.causal; at.qkv = qkv; at.o = o; at.lse = lse; at.stream = s;
+    if ((rc = run_attn(at, false))) return rc;
+    GemmArgs g3 = mk(x, 0, 0, x.M, x.H, x.Hl, o, p->w_o, y_attn, ws, ws_bytes, s);
+    if (x.row_epi) { g3.bias = p->b_o; g3.resid = x_attn; }
+    if ((rc = run_gemm(g3))) return rc;
+    // MLP block: column-parallel up-projection + GeLU, row-parallel down-projection
+    GemmArgs g4 = mk(x, 0, 0, x.M, x.Il, x.H, x_mlp, p->w_up, g, ws, ws_bytes, s);
+    g4.bias = p->b_up; g4.aux = u; g4.epi = EPI_GELU;
+    if ((rc = run_gemm(g4))) return rc;
+    GemmArgs g5 = mk(x, 0, 0, x.M, x.H, x.Il, g, p->w_dn, y_mlp, ws, ws_bytes, s);
+    if (x.row_epi) { g5.bias = p->b_dn; g5.resid = x_mlp; }
+    return run_gemm(g5);
+}
+
+int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void* x_attn,
+                 const void* x_mlp, const void* dy_attn, const void* dy_mlp, const void* saved,
+                 const tp_layer_grads* gr, void* dx_attn, void* dx_mlp, void* ws, size_t ws_bytes,
+                 void* hip_stream) {
+    Dims x;
+    int rc = resolve(desc, &x);
+    if (rc != TPL_OK) return rc;
+    if (!p || !gr || !x_attn || !x_mlp || !dy_attn || !dy_mlp || !saved || !dx_attn || !dx_mlp || !ws)
+        return TPL_EINVAL;
+    if (!p->w_qkv || !p->w_o || !p->w_up || !p->w_dn) return TPL_EINVAL;
+    if (!gr->dw_qkv || !gr->db_qkv || !gr->dw_o || !gr->dw_up || !gr->db_up || !gr->dw_dn) return TPL_EINVAL;
+    if (x.row_epi && (!gr->db_o || !gr->db_dn)) return TPL_EINVAL;
+    const void* ptrs[] = {x_attn, x_mlp, dy_attn, dy_mlp, saved, dx_attn, dx_mlp, ws, p->w_qkv, p->w_o,
+                          p->w_up, p->w_dn, gr->dw_qkv, gr->db_qkv, gr->dw_o, gr->db_o, gr->dw_up,
+                          gr->db_up, gr->dw_dn, gr->db_dn};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    BwdWs W;
+    bwd_layout(x, &W);
+    if (ws_bytes < W.total) return TPL_EWORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    tp_layer_saved_layout L;
+    saved_layout(x, &L);
+    const char* sv = (const char*)saved;
+    const void *qkv = sv + L.qkv, *o = sv + L.o, *u = sv + L.u, *g = sv + L.g;
+    const float* lse = (const float*)(sv + L.lse);
+    char* w = (char*)ws;
+    void *du = w + W.du, *d_o = w + W.d_o, *dqkv = w + W.dqkv, *gws = w + W.gemm;
+    float *dsum = (float*)(w + W.dsum), *cs = (float*)(w + W.colsum);
+    size_t gsz = W.total - W.gemm;
+
+    // MLP block.  dU = (dy_m W_dn^T) * gelu'(U) in one GEMM epilogue.
+    GemmArgs b5 = mk(x, 0, 1, x.M, x.Il, x.H, dy_mlp, p->w_dn, du, gws, gsz, s);
+    b5.aux = const_cast<void*>(u); b5.epi = EPI_DGELU;
+    if ((rc = run_gemm(b5))) return rc;
+    GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, gws, gsz, s);
+    if ((rc = run_gemm(w5))) return rc;
+    GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, gws, gsz, s);
+    if ((rc = run_gemm(w4))) return rc;
+    if (colsum(x.dtype, x.M, x.Il, du, gr->db_up, cs, s) != hipSuccess) return TPL_EHIP;
+    GemmArgs d4 = mk(x, 0, 1, x.M, x.H, x.Il, du, p->w_up, dx_mlp, gws, gsz, s);
+    if (x.row_epi) d4.resid = dy_mlp;
+    if ((rc = run_gemm(d4))) return rc;
+    if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_mlp, gr->db_dn, cs, s) != hipSuccess) return TPL_EHIP;
+
+    // attention block
+    GemmArgs d3 = mk(x, 0, 1, x.M, x.Hl, x.H, dy_attn, p->w_o, d_o, gws, gsz, s);
+    if ((rc = run_gemm(d3))) return rc;
+    GemmArgs w3 = mk(x, 1, 0, x.Hl, x.H, x.M, o, dy_attn, gr->dw_o, gws, gsz, s);
+    if ((rc = run_gemm(w3))) return rc;
+    if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_attn, gr->db_o, cs, s) != hipSuccess) return TPL_EHIP;
+    AttnArgs at{};
+    at.dtype = x.dtype; at.B = (int)x.B; at.S = (int)x.S; at.nl = (int)x.nl; at.dh = (int)x.dh;
+    at.causal = x.causal; at.qkv = qkv; at.o = const_cast<void*>(o); at.lse = const_cast<float*>(lse);
+    at.d_o = d_o; at.dqkv = dqkv; at.dsum = dsum; at.stream = s;
+    if ((rc = run_attn(at, true))) return rc;
+    GemmArgs w1 = mk(x, 1, 0, x.H, 3 * x.Hl, x.M, x_attn, dqkv, gr->dw_qkv, gws, gsz, s);
+    if ((rc = run_gemm(w1))) return rc;
+    if (colsum(x.dtype, x.M, 3 * x.Hl, dqkv, gr->db_qkv, cs, s) != hipSuccess) return TPL_EHIP;
+    GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, gws, gsz, s);
+    if (x.row_epi) d1.resid = dy_attn;
+    return run_gemm(d1);
+}
+
+size_t tp_layer_gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K) {
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return std::max(gemm_ws(dtype, M, N, K), ALIGN);
+}
+
+int tp_layer_gemm(int dtype, int trans_a, int trans_b, int64_t M, int64_t N, int64_t K,
+                  const void* A, const void* B, void* C, const void* bias, const void* resid,
+                  void* aux, int epi, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (dtype != TPL_F32 && dtype != TPL_BF16) return TPL_EINVAL;
+    if (M <= 0 || N <= 0 || K <= 0 || !A || !B || !C || !ws) return TPL_EINVAL;
+    if (epi != TPL_EPI_NONE && epi != TPL_EPI_GELU && epi != TPL_EPI_DGELU) return TPL_EINVAL;
+    if (epi != TPL_EPI_NONE && !aux) return TPL_EINVAL;
+    int64_t q = dtype == TPL_BF16 ? 8 : 4;
+    if (M % q || N % q || K % q) return TPL_EUNSUPPORTED;
+    const void* ptrs[] = {A, B, C, bias, resid, aux, ws};
+    for (const void* pp : ptrs) if (misaligned(pp)) return TPL_EALIGN;
+    if (ws_bytes < tp_layer_gemm_workspace_bytes(dtype, M, N, K)) return TPL_EWORKSPACE;
+    GemmArgs g{};
+    g.dtype = dtype; g.trans_a = trans_a != 0; g.trans_b = trans_b != 0; g.M = M; g.N = N; g.K = K;
+    g.A = A; g.B = B; g.C = C; g.bias = bias; g.resid = resid; g.aux = aux; g.epi = epi;
+    g.ws = ws; g.ws_bytes = ws_bytes; g.stream = (hipStream_t)hip_stream;
+    return run_gemm(g);
+}
+
+static int attn_check(int dtype, int B, int S, int nl, int dh) {
+    if (dtype != TPL_F32 && dtype != TPL_BF16) return TPL_EINVAL;
+    if (B <= 0 || S <= 0 || nl <= 0 || dh <= 0) return TPL_EINVAL;
+    if (dh > 256 || (int64_t)nl * dh % (dtype == TPL_BF16 ? 8 : 4)) return TPL_EUNSUPPORTED;
+    return TPL_OK;
+}
+
+int tp_layer_attn_fwd(int dtype, int B, int S, int nl, int dh, int causal, const void* qkv, void* o,
+                      float* lse, void* hip_stream) {
+    int rc = attn_check(dtype, B, S, nl, dh);
+    if (rc) return rc;
+    if (!qkv || !o || !lse) return TPL_EINVAL;
+    if (misaligned(qkv) || misaligned(o) || misaligned(lse)) return TPL_EALIGN;
+    AttnArgs a{};
+    a.dtype = dtype; a.B = B; a.S = S; a.nl = nl; a.dh = dh; a.causal = causal != 0;
+    a.qkv = qkv; a.o = o; a.lse = lse; a.stream = (hipStream_t)hip_stream;
+    return run_attn(a, false);
+}
+
+int tp_layer_attn_bwd(int dtype, int B, int S, int nl, int dh, int causal, const void* qkv,
+                      const void* o, const float* lse, const void* d_o, void* dqkv,
+                      float* d_scratch, void* hip_stream) {
+    int rc = attn_check(dtype, B, S, nl, dh);
+    if (rc) return rc;
+    if (!qkv || !o || !lse || !d_o || !dqkv || !d_scratch) return TPL_EINVAL;
+    const void* ptrs[] = {qkv, o, lse, d_o, dqkv, d_scratch};
+    for (const void* pp : ptrs) if (misaligned(pp)) return TPL_EALIGN;
+    AttnArgs a{};
+    a.dtype = dtype; a.B = B; a.S = S; a.nl = nl; a.dh = dh; a.causal = causal != 0;
+    a.qkv = qkv; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse); a.d_o = d_o;
+    a.dqkv = dqkv; a.dsum = d_scratch; a.stream = (hipStream_t)hip_stream;
+    return run_attn(a, true);
+}
+
+const char* tp_layer_strerror(int status) {
+    switch (status) {
+        case TPL_OK: return "ok";
+        case TPL_EINVAL: return "invalid argument (null pointer, non-positive or non-dividing size)";
+        case TPL_EUNSUPPORTED: return "valid layer but unsupported shape or dtype";
+        case TPL_EWORKSPACE: return "workspace too small";
+        case TPL_EALIGN: return "pointer not 16-byte aligned";
+        case TPL_EHIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

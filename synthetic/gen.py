@@ -4,6 +4,9 @@ Element i of a tensor drawn with seed s uses the two 64-bit words
 splitmix64(s + 2i) and splitmix64(s + 2i + 1); the result therefore does not
 depend on chunking or on the order tensors are generated in.
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 _GOLDEN = np.uint64(0x9E3779B97F4A7C15)
@@ -26,19 +29,28 @@ def _unit_open(bits):
     return ((bits >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
 
 
-def normal(seed, n, sigma=1.0, chunk=1 << 22):
+def _fill(out, base, lo, hi, sigma):
+    idx = np.arange(lo, hi, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        c0 = base + idx * np.uint64(2)
+    u1 = _unit_open(_splitmix64(c0))
+    u2 = _unit_open(_splitmix64(c0 + np.uint64(1)))
+    z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    out[lo:hi] = (z * sigma).astype(np.float32)
+
+
+def normal(seed, n, sigma=1.0, chunk=1 << 20):
     """n samples of N(0, sigma^2) as float32 (generated in float64, then cast)."""
     out = np.empty(n, dtype=np.float32)
     base = np.uint64((int(seed) * 0x100000001B3) & 0xFFFFFFFFFFFFFFFF)
-    for lo in range(0, n, chunk):
-        hi = min(n, lo + chunk)
-        idx = np.arange(lo, hi, dtype=np.uint64)
-        with np.errstate(over="ignore"):
-            c0 = base + idx * np.uint64(2)
-        u1 = _unit_open(_splitmix64(c0))
-        u2 = _unit_open(_splitmix64(c0 + np.uint64(1)))
-        z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
-        out[lo:hi] = (z * sigma).astype(np.float32)
+    spans = [(lo, min(n, lo + chunk)) for lo in range(0, n, chunk)]
+    workers = min(8, os.cpu_count() or 1, len(spans))
+    if workers <= 1:
+        for lo, hi in spans:
+            _fill(out, base, lo, hi, sigma)
+    else:
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(lambda s: _fill(out, base, s[0], s[1], sigma), spans))
     return out
 
 
