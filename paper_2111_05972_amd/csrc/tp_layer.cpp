@@ -110,8 +110,12 @@ int run_attn(AttnArgs& a, bool bwd) {
     return e == hipSuccess ? TPL_OK : TPL_EHIP;
 }
 
+// Scratch handed to every GEMM of one entry-point call.
+struct GemmScratch { void* ws; size_t bytes; hipStream_t stream; };
+
 GemmArgs mk(const Dims& x, int ta, int tb, int64_t M, int64_t N, int64_t K, const void* A,
-            const void* B, void* C, void* ws, size_t ws_bytes, hipStream_t s) {
+            const void* B, void* C, GemmScratch& sc) {
+    void* ws = sc.ws; size_t ws_bytes = sc.bytes; hipStream_t s = sc.stream;
     GemmArgs g{};
     g.dtype = x.dtype; g.trans_a = ta; g.trans_b = tb; g.M = M; g.N = N; g.K = K;
     g.A = A; g.B = B; g.C = C; g.epi = EPI_NONE; g.ws = ws; g.ws_bytes = ws_bytes; g.stream = s;
@@ -169,23 +173,24 @@ int tp_layer_fwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     char* sv = (char*)saved;
     void *qkv = sv + L.qkv, *o = sv + L.o, *u = sv + L.u, *g = sv + L.g;
     float* lse = (float*)(sv + L.lse);
+    GemmScratch sc{ws, ws_bytes, s};
 
     // attention block: column-parallel fused QKV, attention on the local heads, row-parallel out-proj
-    GemmArgs g1 = mk(x, 0, 0, x.M, 3 * x.Hl, x.H, x_attn, p->w_qkv, qkv, ws, ws_bytes, s);
+    GemmArgs g1 = mk(x, 0, 0, x.M, 3 * x.Hl, x.H, x_attn, p->w_qkv, qkv, sc);
     g1.bias = p->b_qkv;
     if ((rc = run_gemm(g1))) return rc;
     AttnArgs at{};
     at.dtype = x.dtype; at.B = (int)x.B; at.S = (int)x.S; at.nl = (int)x.nl; at.dh = (int)x.dh;
     at.causal = x.causal; at.qkv = qkv; at.o = o; at.lse = lse; at.stream = s;
     if ((rc = run_attn(at, false))) return rc;
-    GemmArgs g3 = mk(x, 0, 0, x.M, x.H, x.Hl, o, p->w_o, y_attn, ws, ws_bytes, s);
+    GemmArgs g3 = mk(x, 0, 0, x.M, x.H, x.Hl, o, p->w_o, y_attn, sc);
     if (x.row_epi) { g3.bias = p->b_o; g3.resid = x_attn; }
     if ((rc = run_gemm(g3))) return rc;
     // MLP block: column-parallel up-projection + GeLU, row-parallel down-projection
-    GemmArgs g4 = mk(x, 0, 0, x.M, x.Il, x.H, x_mlp, p->w_up, g, ws, ws_bytes, s);
+    GemmArgs g4 = mk(x, 0, 0, x.M, x.Il, x.H, x_mlp, p->w_up, g, sc);
     g4.bias = p->b_up; g4.aux = u; g4.epi = EPI_GELU;
     if ((rc = run_gemm(g4))) return rc;
-    GemmArgs g5 = mk(x, 0, 0, x.M, x.H, x.Il, g, p->w_dn, y_mlp, ws, ws_bytes, s);
+    GemmArgs g5 = mk(x, 0, 0, x.M, x.H, x.Il, g, p->w_dn, y_mlp, sc);
     if (x.row_epi) { g5.bias = p->b_dn; g5.resid = x_mlp; }
     return run_gemm(g5);
 }
@@ -219,25 +224,26 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     void *du = w + W.du, *d_o = w + W.d_o, *dqkv = w + W.dqkv, *gws = w + W.gemm;
     float *dsum = (float*)(w + W.dsum), *cs = (float*)(w + W.colsum);
     size_t gsz = W.total - W.gemm;
+    GemmScratch sc{gws, gsz, s};
 
     // MLP block.  dU = (dy_m W_dn^T) * gelu'(U) in one GEMM epilogue.
-    GemmArgs b5 = mk(x, 0, 1, x.M, x.Il, x.H, dy_mlp, p->w_dn, du, gws, gsz, s);
+    GemmArgs b5 = mk(x, 0, 1, x.M, x.Il, x.H, dy_mlp, p->w_dn, du, sc);
     b5.aux = const_cast<void*>(u); b5.epi = EPI_DGELU;
     if ((rc = run_gemm(b5))) return rc;
-    GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, gws, gsz, s);
+    GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, sc);
     if ((rc = run_gemm(w5))) return rc;
-    GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, gws, gsz, s);
+    GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, sc);
     if ((rc = run_gemm(w4))) return rc;
     if (colsum(x.dtype, x.M, x.Il, du, gr->db_up, cs, s) != hipSuccess) return TPL_EHIP;
-    GemmArgs d4 = mk(x, 0, 1, x.M, x.H, x.Il, du, p->w_up, dx_mlp, gws, gsz, s);
+    GemmArgs d4 = mk(x, 0, 1, x.M, x.H, x.Il, du, p->w_up, dx_mlp, sc);
     if (x.row_epi) d4.resid = dy_mlp;
     if ((rc = run_gemm(d4))) return rc;
     if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_mlp, gr->db_dn, cs, s) != hipSuccess) return TPL_EHIP;
 
     // attention block
-    GemmArgs d3 = mk(x, 0, 1, x.M, x.Hl, x.H, dy_attn, p->w_o, d_o, gws, gsz, s);
+    GemmArgs d3 = mk(x, 0, 1, x.M, x.Hl, x.H, dy_attn, p->w_o, d_o, sc);
     if ((rc = run_gemm(d3))) return rc;
-    GemmArgs w3 = mk(x, 1, 0, x.Hl, x.H, x.M, o, dy_attn, gr->dw_o, gws, gsz, s);
+    GemmArgs w3 = mk(x, 1, 0, x.Hl, x.H, x.M, o, dy_attn, gr->dw_o, sc);
     if ((rc = run_gemm(w3))) return rc;
     if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_attn, gr->db_o, cs, s) != hipSuccess) return TPL_EHIP;
     AttnArgs at{};
@@ -245,10 +251,10 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     at.causal = x.causal; at.qkv = qkv; at.o = const_cast<void*>(o); at.lse = const_cast<float*>(lse);
     at.d_o = d_o; at.dqkv = dqkv; at.dsum = dsum; at.stream = s;
     if ((rc = run_attn(at, true))) return rc;
-    GemmArgs w1 = mk(x, 1, 0, x.H, 3 * x.Hl, x.M, x_attn, dqkv, gr->dw_qkv, gws, gsz, s);
+    GemmArgs w1 = mk(x, 1, 0, x.H, 3 * x.Hl, x.M, x_attn, dqkv, gr->dw_qkv, sc);
     if ((rc = run_gemm(w1))) return rc;
     if (colsum(x.dtype, x.M, 3 * x.Hl, dqkv, gr->db_qkv, cs, s) != hipSuccess) return TPL_EHIP;
-    GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, gws, gsz, s);
+    GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, sc);
     if (x.row_epi) d1.resid = dy_attn;
     return run_gemm(d1);
 }

@@ -19,7 +19,8 @@ def _draw(seed, shape, sigma, dtype):
     return synthetic.quantize(synthetic.normal(seed, n, sigma), dtype).reshape(shape)
 
 
-GEMM_SHAPES = [(256, 256, 64), (520, 264, 136), (1000, 776, 2056), (64, 1536, 4096), (8, 8, 8), (264, 512, 72)]
+GEMM_SHAPES = [(256, 256, 64), (520, 264, 136), (1000, 776, 2056), (64, 1536, 4096), (8, 8, 8), (264, 512, 72),
+               (2048, 1536, 3080), (4104, 4360, 520)]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
