@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--config", default="5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs one tensor-parallel rank's shard on ONE GPU; "
@@ -53,6 +55,14 @@ def main():
 
     pkg.load_library()   # raises if the HIP library is missing: there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
+        return
     key = int(args.config) if args.config.isdigit() else args.config
     cfg = synthetic.get_config(key)
     dt = pkg.TPL_F32 if cfg.dtype == "f32" else pkg.TPL_BF16
@@ -102,49 +112,38 @@ def main():
     bwd_ms = timed(lambda: layer.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m,
                                           stream=stream), n_split)
 
-    # dominant kernel: the GEMM kernel, each of the step's 12 launches timed with events on the
-    # launch stream at the shapes and transposes of the step (operands are the step's own buffers).
+    # dominant kernel: the GEMM kernel.  Its 12 launches per step are timed inside real steps: the
+    # library brackets each GEMM launch with HIP events on the launch stream (tp_layer_profile).
     roofline = None
-    per_gemm = {}
     if not args.no_kernel_timing:
-        sv = layer.saved_tensors()
-        tdt = layer.tdtype
-        M, H, Hl, Il = cfg.tokens, cfg.hidden, cfg.local_attn, cfg.local_mlp
-        scratch = {n: torch.empty(s, dtype=tdt, device="cuda") for n, s in
-                   {"mil": (M, Il), "mhl": (M, Hl), "m3": (M, 3 * Hl)}.items()}
-        ops = {
-            "qkv_fwd": (x["x_a"], p["w_qkv"], sv["QKV"]), "out_fwd": (sv["O"], p["w_o"], y_a),
-            "up_fwd": (x["x_m"], p["w_up"], scratch["mil"]), "down_fwd": (sv["G"], p["w_dn"], y_m),
-            "down_dgrad": (x["dy_m"], p["w_dn"], scratch["mil"]), "down_wgrad": (sv["G"], x["dy_m"], grads["dw_dn"]),
-            "up_wgrad": (x["x_m"], scratch["mil"], grads["dw_up"]), "up_dgrad": (scratch["mil"], p["w_up"], dx_m),
-            "out_dgrad": (x["dy_a"], p["w_o"], scratch["mhl"]), "out_wgrad": (sv["O"], x["dy_a"], grads["dw_o"]),
-            "qkv_wgrad": (x["x_a"], scratch["m3"], grads["dw_qkv"]), "qkv_dgrad": (scratch["m3"], p["w_qkv"], dx_a),
-        }
-        tot_ms, tot_fl = 0.0, 0.0
+        names = [g[0] for g in gemm_list(cfg)]
+        flops = {g[0]: 2.0 * g[3] * g[4] * g[5] for g in gemm_list(cfg)}
+        shapes = {g[0]: {"M": g[3], "N": g[4], "K": g[5]} for g in gemm_list(cfg)}
         reps = max(3, min(args.steps, 10))
-        for name, ta, tb, gm, gn, gk in gemm_list(cfg):
-            A, Bm, Cm = ops[name]
-            call = lambda: pkg.tp_layer_gemm(dt, ta, tb, gm, gn, gk, A, Bm, Cm, ws=layer.ws, stream=stream)  # noqa: E731
-            call()
-            ms = timed(call, reps)
-            fl = 2.0 * gm * gn * gk
-            per_gemm[name] = {"M": gm, "N": gn, "K": gk, "ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 1)}
-            tot_ms += ms
-            tot_fl += fl
+        pkg.tp_layer_profile(1)
+        for _ in range(reps):
+            step()
+        torch.cuda.synchronize()
+        ms = pkg.tp_layer_profile_read()
+        pkg.tp_layer_profile(0)
+        assert len(ms) == 12 * reps, len(ms)
+        per = {n: sum(ms[i] for i in range(len(ms)) if names[i % 12] == n) / reps for n in names}
+        tot_ms, tot_fl = sum(per.values()), sum(flops.values())
         achieved = tot_fl / (tot_ms * 1e-3) / 1e12
         traffic = None
         tpath = os.path.join(ROOT, "profiles", "traffic.json")
         if os.path.exists(tpath):
             try:
-                traffic = json.load(open(tpath)).get(cfg.name)
+                traffic = json.load(open(tpath)).get(cfg.name, {}).get("bytes_per_launch")
             except Exception:
                 traffic = None
+        launches = {n: {**shapes[n], "ms": round(per[n], 4), "tflops": round(flops[n] / per[n] / 1e9, 1)} for n in names}
         roofline = {"kernel": "gemm_bf16_kernel (12 launches per step)" if cfg.dtype == "bf16" else "gemm_simple_kernel",
                     "bound": "mfma" if cfg.dtype == "bf16" else "alu",
                     "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                     "frac": round(achieved / peak, 4), "traffic": traffic,
-                    "flops_per_launch_avg": tot_fl / 12, "avg_launch_ms": round(tot_ms / 12, 4),
-                    "gemm_ms_per_step": round(tot_ms, 4), "launches": per_gemm}
+                    "flops_per_launch": tot_fl / 12, "avg_launch_ms": round(tot_ms / 12, 4),
+                    "gemm_ms_per_step": round(tot_ms, 4), "launches": launches}
 
     cpu_baseline = None
     max_err = None

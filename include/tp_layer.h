@@ -163,6 +163,14 @@ int tp_layer_attn_bwd(int dtype, int B, int S, int nl, int dh, int causal,
                       const void* qkv, const void* o, const float* lse, const void* d_o,
                       void* dqkv, float* d_scratch, void* hip_stream);
 
+/* Diagnostics for benchmarks (not thread-safe, off by default).  tp_layer_profile(1) makes every
+ * GEMM launched by this library (inside tp_layer_fwd / tp_layer_bwd / tp_layer_gemm) be bracketed by
+ * two HIP events on its launch stream and restarts the record; tp_layer_profile(0) stops.
+ * tp_layer_profile_read waits for the recorded launches (at most 4096, in launch order), writes their
+ * durations in milliseconds to ms_out[0..*count) and restarts the record.  ms_out is HOST memory. */
+int tp_layer_profile(int enable);
+int tp_layer_profile_read(float* ms_out, int capacity, int* count);
+
 /* Static description of a status code. */
 const char* tp_layer_strerror(int status);
 

@@ -71,6 +71,8 @@ def load_library():
         "tp_layer_gemm": (ci, [ci, ci, ci, i64, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp, ci, _vp, sz, _vp]),
         "tp_layer_attn_fwd": (ci, [ci, ci, ci, ci, ci, ci, _vp, _vp, _vp, _vp]),
         "tp_layer_attn_bwd": (ci, [ci, ci, ci, ci, ci, ci, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+        "tp_layer_profile": (ci, [ci]),
+        "tp_layer_profile_read": (ci, [ctypes.POINTER(ctypes.c_float), ci, ctypes.POINTER(ci)]),
         "tp_layer_strerror": (ctypes.c_char_p, [ci]),
     }
     for name, (res, args) in sig.items():
@@ -163,6 +165,20 @@ def tp_layer_bwd(desc, params, x_attn, x_mlp, dy_attn, dy_mlp, saved, grads, dx_
     if check and rc != TPL_OK:
         raise TpLayerError(rc, "tp_layer_bwd")
     return rc
+
+
+def tp_layer_profile(enable):
+    return load_library().tp_layer_profile(int(bool(enable)))
+
+
+def tp_layer_profile_read(capacity=4096):
+    """Durations (ms) of the GEMM launches recorded since profiling was enabled, in launch order."""
+    buf = (ctypes.c_float * capacity)()
+    n = ctypes.c_int(0)
+    rc = load_library().tp_layer_profile_read(buf, capacity, ctypes.byref(n))
+    if rc != TPL_OK:
+        raise TpLayerError(rc, "tp_layer_profile_read")
+    return [buf[i] for i in range(n.value)]
 
 
 def tp_layer_gemm_workspace_bytes(dtype, M, N, K):

@@ -96,10 +96,30 @@ void bwd_layout(const Dims& x, BwdWs* W) {
 
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
+// Diagnostic timing of GEMM launches with HIP events on the launch stream (off by default).
+struct GemmProfile {
+    static constexpr int CAP = 4096;
+    bool on = false;
+    int n = 0;
+    hipEvent_t start[CAP], stop[CAP];
+    bool created[CAP] = {};
+} g_prof;
+
 int run_gemm(GemmArgs& g) {
     hipError_t e;
+    int slot = -1;
+    if (g_prof.on && g_prof.n < GemmProfile::CAP) {
+        slot = g_prof.n++;
+        if (!g_prof.created[slot]) {
+            if (hipEventCreate(&g_prof.start[slot]) != hipSuccess || hipEventCreate(&g_prof.stop[slot]) != hipSuccess)
+                return TPL_EHIP;
+            g_prof.created[slot] = true;
+        }
+        if (hipEventRecord(g_prof.start[slot], g.stream) != hipSuccess) return TPL_EHIP;
+    }
     if (g.dtype == BF16 && gemm_bf16_supported(g)) e = gemm_bf16(g);
     else e = gemm_simple(g);
+    if (slot >= 0 && hipEventRecord(g_prof.stop[slot], g.stream) != hipSuccess) return TPL_EHIP;
     return e == hipSuccess ? TPL_OK : TPL_EHIP;
 }
 
@@ -315,6 +335,24 @@ int tp_layer_attn_bwd(int dtype, int B, int S, int nl, int dh, int causal, const
     a.qkv = qkv; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse); a.d_o = d_o;
     a.dqkv = dqkv; a.dsum = d_scratch; a.stream = (hipStream_t)hip_stream;
     return run_attn(a, true);
+}
+
+int tp_layer_profile(int enable) {
+    g_prof.on = enable != 0;
+    g_prof.n = 0;
+    return TPL_OK;
+}
+
+int tp_layer_profile_read(float* ms_out, int capacity, int* count) {
+    if (!ms_out || !count || capacity < 0) return TPL_EINVAL;
+    int n = g_prof.n < capacity ? g_prof.n : capacity;
+    for (int i = 0; i < n; ++i) {
+        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) return TPL_EHIP;
+        if (hipEventElapsedTime(&ms_out[i], g_prof.start[i], g_prof.stop[i]) != hipSuccess) return TPL_EHIP;
+    }
+    *count = n;
+    g_prof.n = 0;
+    return TPL_OK;
 }
 
 const char* tp_layer_strerror(int status) {
