@@ -45,7 +45,8 @@ _lib = None
 
 
 def library_path():
-    return os.path.join(_HERE, _LIB_NAME)
+    """The in-tree library; TPL_LIBRARY may name another build of the same sources (tuning experiments)."""
+    return os.environ.get("TPL_LIBRARY") or os.path.join(_HERE, _LIB_NAME)
 
 
 def load_library():

@@ -12,9 +12,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x",
          "-Wno-unused-command-line-argument", "-Wno-option-ignored"]
 
 
-def build(verbose=False, extra=()):
+def build(verbose=False, extra=(), out=LIB):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + list(extra) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    cmd = [hipcc] + FLAGS + list(extra) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -23,9 +23,15 @@ def build(verbose=False, extra=()):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out:
         print(out)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    build(verbose=True, extra=sys.argv[1:])
-    print("built", LIB)
+    args = sys.argv[1:]
+    out = LIB
+    if "-o" in args:            # build a variant beside the default library (tuning experiments)
+        i = args.index("-o")
+        out = os.path.abspath(args[i + 1])
+        del args[i:i + 2]
+    build(verbose=True, extra=args, out=out)
+    print("built", out)

@@ -2,6 +2,8 @@
 //
 // Tile and pipeline.  A 256-thread workgroup (4 wavefronts, 2 x 2) owns a 256 x 256 output tile;
 // each wavefront accumulates 128 x 128 as 4 x 4 MFMA 32x32x16 blocks (256 accumulator registers).
+// Three smaller variants (256 x 192, 192 x 192, 128 x 128) exist for GEMMs whose 256 x 256 tile count
+// fills the last round over the compute units badly or whose K is short; the host picks by estimate.
 // K is walked in stages of 32 through a 4-deep LDS ring (4 x 32 KiB) that is filled by
 // buffer_load ... lds: global memory goes straight into LDS, no staging registers, and anything
 // outside the matrix is zero filled by the buffer bounds check.  Loads run about 3.5 stages ahead of
@@ -25,6 +27,8 @@
 // contiguous bytes of a row.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "device_math.h"
 #include "kernels.h"
 
@@ -39,15 +43,21 @@ typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 constexpr int DK = 32;                      // k per stage
-constexpr int DSTAGES = 4;
-constexpr int DT = 256;                     // tile edge
-constexpr int D_OP_BYTES = DT * DK * 2;     // one operand tile of one stage: 16 KiB
-constexpr int D_STAGE_BYTES = 2 * D_OP_BYTES;
-constexpr int D_LDS_BYTES = DSTAGES * D_STAGE_BYTES;
 constexpr unsigned OOB_OFFSET = 0xFFFFFFF0u;   // beyond any buffer this kernel accepts
-constexpr int EROW = 4 * 32 * 4 + 16;          // one 128-float row of a wavefront's epilogue staging
-constexpr int EWAVE = 32 * EROW;
-static_assert(4 * EWAVE <= D_LDS_BYTES, "epilogue staging must fit in the ring");
+
+// Tile variant: 2 x 2 wavefronts, each owning TM x TN MFMA 32x32 blocks -> a (64 TM) x (64 TN) tile.
+template <int TM_, int TN_, int STAGES_>
+struct Tile {
+    static constexpr int TM = TM_, TN = TN_, STAGES = STAGES_;
+    static constexpr int BM = 64 * TM, BN = 64 * TN;
+    static constexpr int A_BYTES = BM * DK * 2, B_BYTES = BN * DK * 2;   // one stage of each operand
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LOADS = TM + TN;                                // direct loads per lane and stage
+    static constexpr int EROW = TN * 32 * 4 + 16;                        // staged epilogue row of a wavefront
+    static constexpr int EWAVE = 32 * EROW;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES > 4 * EWAVE ? STAGES * STAGE_BYTES : 4 * EWAVE;
+    static_assert((STAGES - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
+};
 
 struct GemmParams {
     const bf16_t* A; const bf16_t* B; bf16_t* C;
@@ -61,8 +71,21 @@ struct GemmParams {
 // ---- LDS layouts -------------------------------------------------------------------------------
 // K-major stage tile: 64-byte rows (32 k), four 16-byte chunks, swizzled by row.
 __device__ __forceinline__ int swz_k32(int row) { return (row >> 2) & 3; }
-// MN-major stage tile: 512-byte rows (256 m or n) per k, thirty-two 16-byte chunks, swizzled by k.
-__device__ __forceinline__ int swz_mn(int k) { return (k & 3) << 2; }
+// MN-major stage tile: one row of R (m or n) bf16 per k = R/8 16-byte chunks.  A transposing read
+// touches four consecutive k at the same columns, so consecutive k are displaced by 64 bytes:
+// XOR of chunk bits 2-3 when the chunk count is a power of two, a rotation otherwise.
+template <int R> __device__ __forceinline__ int mn_swz(int c, int k) {
+    constexpr int CPR = R / 8;
+    if ((CPR & (CPR - 1)) == 0) return c ^ ((k & 3) << 2);
+    int x = c + ((k & 3) << 2);
+    return x >= CPR ? x - CPR : x;
+}
+template <int R> __device__ __forceinline__ int mn_unswz(int c, int k) {
+    constexpr int CPR = R / 8;
+    if ((CPR & (CPR - 1)) == 0) return c ^ ((k & 3) << 2);
+    int x = c - ((k & 3) << 2);
+    return x < 0 ? x + CPR : x;
+}
 
 // Raw buffer descriptor over `bytes` bytes at p (stride 0): loads at offsets >= bytes return zero
 // instead of touching memory.
@@ -85,14 +108,16 @@ __device__ __forceinline__ void buffer_load_lds_b128(i32x4 rsrc, unsigned lds_ad
                  :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory", "m0");
 }
 
-// Byte offsets (relative to the operand base, for tile origin mn0 and k = 0) of the four 16-byte
-// chunks this lane fetches per stage; chunk j of wavefront w lands in LDS block w*4 + j at 16*lane.
-template <bool KMAJ>
-__device__ __forceinline__ void dma_offsets(unsigned (&off)[4], bool (&mn_ok)[4], int& kcol, int ld,
+// Byte offsets (relative to the operand base, for tile origin mn0 and k = 0) of the T 16-byte chunks
+// this lane fetches per stage (operand tile of R = 64 T rows); chunk j of wavefront w lands in LDS
+// block w*T + j (1 KiB blocks) at 16*lane.
+template <bool KMAJ, int T>
+__device__ __forceinline__ void dma_offsets(unsigned (&off)[T], bool (&mn_ok)[T], int& kcol, int ld,
                                             int mn0, int MN, int wave, int lane) {
+    constexpr int R = 64 * T;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        int block = wave * 4 + j;
+    for (int j = 0; j < T; ++j) {
+        int block = wave * T + j;
         if (KMAJ) {
             int row = block * 16 + (lane >> 2);
             int c = (lane & 3) ^ swz_k32(row);
@@ -100,8 +125,9 @@ __device__ __forceinline__ void dma_offsets(unsigned (&off)[4], bool (&mn_ok)[4]
             mn_ok[j] = true;                                // rows beyond MN fall outside the buffer
             off[j] = (unsigned)(((int64_t)(mn0 + row) * ld + c * 8) * 2);
         } else {
-            int k = block * 2 + (lane >> 5);
-            int c = (lane & 31) ^ swz_mn(k);
+            int idx = block * 64 + lane;                    // physical chunk index inside the stage tile
+            int k = idx / (R / 8);
+            int c = mn_unswz<R>(idx % (R / 8), k);          // logical chunk stored at that position
             kcol = 0;
             mn_ok[j] = mn0 + c * 8 < MN;
             off[j] = (unsigned)(((int64_t)k * ld + mn0 + c * 8) * 2);
@@ -109,21 +135,21 @@ __device__ __forceinline__ void dma_offsets(unsigned (&off)[4], bool (&mn_ok)[4]
     }
 }
 
-// Stage starting at k0; k >= kend is zero filled (the end of K, or the end of this workgroup's share).
-template <bool KMAJ>
-__device__ __forceinline__ void dma_issue(i32x4 rsrc, unsigned tile_lds, const unsigned (&off)[4],
-                                          const bool (&mn_ok)[4], int kcol, int ld, int k0, int kend, int wave) {
+// Stage starting at k0; k >= kend is zero filled.
+template <bool KMAJ, int T>
+__device__ __forceinline__ void dma_issue(i32x4 rsrc, unsigned tile_lds, const unsigned (&off)[T],
+                                          const bool (&mn_ok)[T], int kcol, int ld, int k0, int kend, int wave) {
     const unsigned step = KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * ld * 2);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < T; ++j) {
         bool ok = KMAJ ? (k0 + kcol < kend) : (mn_ok[j] && k0 < kend);
         unsigned o = ok ? off[j] + step : OOB_OFFSET;
-        buffer_load_lds_b128(rsrc, tile_lds + (wave * 4 + j) * 1024, o);
+        buffer_load_lds_b128(rsrc, tile_lds + (wave * T + j) * 1024, o);
     }
 }
 
 // LDS -> MFMA fragment: rows mn_base + (lane % 32), k = ks*16 + 8*(lane/32) + 0..7.
-template <bool KMAJ>
+template <bool KMAJ, int R>
 __device__ __forceinline__ bf16x8 dma_frag(const char* tile, int mn_base, int ks, int lane) {
     if (KMAJ) {
         int row = mn_base + (lane & 31);
@@ -140,13 +166,17 @@ __device__ __forceinline__ bf16x8 dma_frag(const char* tile, int mn_base, int ks
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             int k = kb + 4 * h + kq;
-            int off = k * (DT * 2) + ((((mn >> 3) ^ swz_mn(k))) << 4) + (mn & 7) * 2;
+            int off = k * (R * 2) + (mn_swz<R>(mn >> 3, k) << 4) + (mn & 7) * 2;
             s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tile + off));
             bf16x4 b = __builtin_bit_cast(bf16x4, v);
             out[4 * h + 0] = b[0]; out[4 * h + 1] = b[1]; out[4 * h + 2] = b[2]; out[4 * h + 3] = b[3];
         }
         return out;
     }
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
 __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
@@ -188,143 +218,146 @@ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, 
     tn = within / rows;
 }
 
-template <bool A_KMAJ, bool B_KMAJ>
+template <typename TL, bool A_KMAJ, bool B_KMAJ>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int TM = TL::TM, TN = TL::TN, BM = TL::BM, BN = TL::BN, DSTAGES = TL::STAGES;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int tile = share_of_block(blockIdx.x, gridDim.x);
-    const int ks0 = 0, ks1 = p.nk;
 
     const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)(A_KMAJ ? p.M : p.K) * p.lda * 2));
     const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
     const unsigned lds0 = (unsigned)(uintptr_t)(lds_void_ptr)smem;
-    constexpr int READS = (A_KMAJ ? 4 : 8) + (B_KMAJ ? 4 : 8);   // LDS reads per fragment set
-    {
-        int tm, tn;
-        tile_coords(tile, p.tiles_m, p.tiles_n, tm, tn);
-        const int m0 = tm * DT, n0 = tn * DT;
-        const int kend = ks1 * DK < p.K ? ks1 * DK : p.K;
+    // per half stage: NM MFMAs, NR LDS reads of the next fragment set, TM+TN direct loads (second half)
+    constexpr int NM = TM * TN;
+    constexpr int NR = (A_KMAJ ? TM : 2 * TM) + (B_KMAJ ? TN : 2 * TN);
+    constexpr int RPM = (NR + NM - 2) / (NM - 1);                 // LDS reads placed after each MFMA
 
-        f32x16 acc[4][4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    int tm, tn;
+    tile_coords(tile, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
 
-        unsigned offa[4], offb[4];
-        bool oka[4], okb[4];
-        int kca, kcb;
-        dma_offsets<A_KMAJ>(offa, oka, kca, p.lda, m0, p.M, wave, lane);
-        dma_offsets<B_KMAJ>(offb, okb, kcb, p.ldb, n0, p.N, wave, lane);
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-        // ring slot of stage s is (s - ks0) % 4; stages >= ks1 are issued too (zero fill, no memory
-        // traffic) so that the number of loads in flight is the same in every iteration.
-        auto issue = [&](int s) {
-            const unsigned buf = lds0 + ((s - ks0) % DSTAGES) * D_STAGE_BYTES;
-            dma_issue<A_KMAJ>(ra, buf, offa, oka, kca, p.lda, s * DK, kend, wave_u);
-            dma_issue<B_KMAJ>(rb, buf + D_OP_BYTES, offb, okb, kcb, p.ldb, s * DK, kend, wave_u);
-        };
-        auto read_frags = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[4], int s, int ks) {
-            const char* buf = smem + ((s - ks0) % DSTAGES) * D_STAGE_BYTES;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) fa[i] = dma_frag<A_KMAJ>(buf, (wm * 4 + i) * 32, ks, lane);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) fb[j] = dma_frag<B_KMAJ>(buf + D_OP_BYTES, (wn * 4 + j) * 32, ks, lane);
-        };
-        auto mma = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[4]) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        };
+    unsigned offa[TM], offb[TN];
+    bool oka[TM], okb[TN];
+    int kca, kcb;
+    dma_offsets<A_KMAJ, TM>(offa, oka, kca, p.lda, m0, p.M, wave, lane);
+    dma_offsets<B_KMAJ, TN>(offb, okb, kcb, p.ldb, n0, p.N, wave, lane);
 
-        issue(ks0); issue(ks0 + 1); issue(ks0 + 2); issue(ks0 + 3);
-        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");        // first stage has landed (8 loads per stage)
-        __builtin_amdgcn_s_barrier();
-        bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
-        read_frags(fa0, fb0, ks0, 0);
+    // ring slot of stage s is s % STAGES; stages past the end of K are issued too (all chunks out of
+    // bounds: zero fill, no memory traffic) so the number of loads in flight never changes.
+    auto issue = [&](int s) {
+        const unsigned buf = lds0 + (s % DSTAGES) * TL::STAGE_BYTES;
+        dma_issue<A_KMAJ, TM>(ra, buf, offa, oka, kca, p.lda, s * DK, p.K, wave_u);
+        dma_issue<B_KMAJ, TN>(rb, buf + TL::A_BYTES, offb, okb, kcb, p.ldb, s * DK, p.K, wave_u);
+    };
+    auto read_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int s, int ks) {
+        const char* buf = smem + (s % DSTAGES) * TL::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = dma_frag<A_KMAJ, BM>(buf, (wm * TM + i) * 32, ks, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[j] = dma_frag<B_KMAJ, BN>(buf + TL::A_BYTES, (wn * TN + j) * 32, ks, lane);
+    };
+    auto mma = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
 
-        for (int kt = ks0; kt < ks1; ++kt) {
-            // first half: math on k-substep 0 while the fragments of substep 1 are read
-            read_frags(fa1, fb1, kt, 1);
-            mma(fa0, fb0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // math first: no LDS wait at the loop top
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x100, READS / 8, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);
-            // stage kt+1 has landed for this wavefront once at most two newer stages are in flight;
-            // after the barrier it has landed for all, and nobody reads stage kt's slot any more.
-            asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            issue(kt + 4);
-            read_frags(fa0, fb0, kt + 1, 0);
-            mma(fa1, fb1);
+    for (int s0 = 0; s0 < DSTAGES; ++s0) issue(s0);
+    wait_vmcnt<(DSTAGES - 1) * TL::LOADS>();                     // first stage has landed
+    __builtin_amdgcn_s_barrier();
+    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    read_frags(fa0, fb0, 0, 0);
+
+    for (int kt = 0; kt < p.nk; ++kt) {
+        // first half: math on k-substep 0 while the fragments of substep 1 are read
+        read_frags(fa1, fb1, kt, 1);
+        mma(fa0, fb0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // math first: no LDS wait at the loop top
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, READS / 8, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        for (int i = 0; i < NM - 1; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         }
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");   // drain the ring before LDS is reused
+        // stage kt+1 has landed for this wavefront once only the newer stages are in flight; after the
+        // barrier it has landed for all, and nobody reads stage kt's slot any more.
+        wait_vmcnt<(DSTAGES - 2) * TL::LOADS>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
+        issue(kt + DSTAGES);
+        read_frags(fa0, fb0, kt + 1, 0);
+        mma(fa1, fb1);
+#pragma unroll
+        for (int i = 0; i < NM; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+    }
+    wait_vmcnt<0>();                                             // drain the ring before LDS is reused
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
 
-        // ---- epilogue: accumulators -> per-wavefront LDS staging -> 16-byte row accesses ----------
-        char* stage = smem + wave * EWAVE;
-        const int er = lane >> 4, ec = (lane & 15) * 8;
-        const int ln = wn * 128 + ec;             // column inside the tile
-        const int gn = n0 + ln;
-        float bias8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (p.bias && gn < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + gn), bias8);
+    // ---- epilogue: accumulators -> per-wavefront LDS staging -> 16-byte row accesses --------------
+    constexpr int LPR = TN * 4;               // lanes per staged row (8 columns each)
+    constexpr int RPP = 64 / LPR;             // rows per pass (lanes beyond RPP*LPR idle when TN = 3)
+    constexpr int PASSES = (32 + RPP - 1) / RPP;
+    char* stage = smem + wave * TL::EWAVE;
+    const int er = lane / LPR, ec = (lane % LPR) * 8;
+    const int gn = n0 + wn * TN * 32 + ec;
+    float bias8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (p.bias && gn < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + gn), bias8);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            // accumulator register v of block (i,j): row (v/4)*8 + (lane/32)*4 + v%4, column j*32 + lane%32
+    for (int i = 0; i < TM; ++i) {
+        // accumulator register v of block (i,j): row (v/4)*8 + (lane/32)*4 + v%4, column j*32 + lane%32
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int row = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                    *reinterpret_cast<float*>(stage + row * EROW + (j * 32 + (lane & 31)) * 4) = acc[i][j][v];
-                }
+            for (int v = 0; v < 16; ++v) {
+                int row = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+                *reinterpret_cast<float*>(stage + row * TL::EROW + (j * 32 + (lane & 31)) * 4) = acc[i][j][v];
+            }
 #pragma unroll
-            for (int pass = 0; pass < 8; ++pass) {
-                const int row = pass * 4 + er;
-                const int lm = (wm * 4 + i) * 32 + row;      // row inside the tile
-                const int gm = m0 + lm;
-                const float4* src = reinterpret_cast<const float4*>(stage + row * EROW + ec * 4);
+        for (int pass = 0; pass < PASSES; ++pass) {
+            const int row = pass * RPP + er;
+            const int gm = m0 + (wm * TM + i) * 32 + row;
+            if (er < RPP && row < 32 && gm < p.M && gn < p.N) {
+                const float4* src = reinterpret_cast<const float4*>(stage + row * TL::EROW + ec * 4);
                 float4 x0 = src[0], x1 = src[1];
-                if (gm < p.M && gn < p.N) {
-                    float v8[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-                    const int64_t idx = (int64_t)gm * p.N + gn;
+                float v8[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                const int64_t idx = (int64_t)gm * p.N + gn;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v8[e] += bias8[e];
-                    if (p.resid) {
-                        float r8[8];
-                        unpack8(*reinterpret_cast<const uint4*>(p.resid + idx), r8);
+                for (int e = 0; e < 8; ++e) v8[e] += bias8[e];
+                if (p.resid) {
+                    float r8[8];
+                    unpack8(*reinterpret_cast<const uint4*>(p.resid + idx), r8);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) v8[e] += r8[e];
-                    }
-                    if (p.epi == EPI_GELU) {
-                        *reinterpret_cast<uint4*>(p.aux + idx) = pack8(v8);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v8[e] = gelu_f(v8[e]);
-                    } else if (p.epi == EPI_DGELU) {
-                        float u8[8];
-                        unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), u8);
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) v8[e] *= gelu_grad_f(u8[e]);
-                    }
-                    *reinterpret_cast<uint4*>(p.C + idx) = pack8(v8);
+                    for (int e = 0; e < 8; ++e) v8[e] += r8[e];
                 }
+                if (p.epi == EPI_GELU) {
+                    *reinterpret_cast<uint4*>(p.aux + idx) = pack8(v8);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v8[e] = gelu_f(v8[e]);
+                } else if (p.epi == EPI_DGELU) {
+                    float u8[8];
+                    unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), u8);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v8[e] *= gelu_grad_f(u8[e]);
+                }
+                *reinterpret_cast<uint4*>(p.C + idx) = pack8(v8);
             }
         }
     }
@@ -335,23 +368,75 @@ bool gemm_bf16_supported(const GemmArgs& a) {
     if (a.M % 8 || a.N % 8 || a.K % 8) return false;
     // 32-bit buffer offsets: operands below 2 GiB
     if (a.M * a.K * 2 >= 0x7FFFFFFFll || a.N * a.K * 2 >= 0x7FFFFFFFll) return false;
-    int64_t tiles = ((a.M + DT - 1) / DT) * ((a.N + DT - 1) / DT);
+    int64_t tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
     return tiles < (1 << 24) && a.K < (1 << 24);
 }
 
 size_t gemm_bf16_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
 
-template <bool AK, bool BK_>
-static hipError_t launch(const GemmParams& p, int grid, hipStream_t s) {
+template <typename TL, bool AK, bool BK_>
+static hipError_t launch(GemmParams p, const GemmArgs& a) {
     static bool attr_set = false;   // raising the dynamic LDS limit is a per-function, one-off call
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<AK, BK_>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<TL, AK, BK_>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_bf16_kernel<AK, BK_>), dim3(grid), dim3(256), D_LDS_BYTES, s, p);
+    p.tiles_m = (int)((a.M + TL::BM - 1) / TL::BM);
+    p.tiles_n = (int)((a.N + TL::BN - 1) / TL::BN);
+    hipLaunchKernelGGL((gemm_bf16_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n), dim3(256),
+                       TL::LDS_BYTES, a.stream, p);
     return hipGetLastError();
+}
+
+template <typename TL>
+static hipError_t launch_layout(const GemmParams& p, const GemmArgs& a) {
+    const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
+    if (a_kmaj && b_kmaj) return launch<TL, true, true>(p, a);
+    if (a_kmaj && !b_kmaj) return launch<TL, true, false>(p, a);
+    if (!a_kmaj && b_kmaj) return launch<TL, false, true>(p, a);
+    return launch<TL, false, false>(p, a);
+}
+
+// Tile variants.  The host launches the one with the least estimated time
+//   (tiles per compute unit, rounded up) x (k-stages) x (time per stage) + (per-tile fixed cost),
+// with per-stage times measured on 8192^3 GEMMs.  The fixed cost (pipeline fill, and an epilogue that
+// is bandwidth-bound because a round's workgroups all reach it together) is paid per round by the
+// variants that fit one workgroup per compute unit and once by those that fit two (192 x 192 and
+// 128 x 128), whose co-resident workgroups overlap each other's fill and epilogue.  So long-K GEMMs
+// with few tiles prefer the big tiles, short-K weight gradients the co-resident ones, and a GEMM
+// whose 256 x 256 tile count fills the last round badly a shape that divides better.
+static int compute_units() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        cus = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+                  ? prop.multiProcessorCount : 256;
+    }
+    return cus;
+}
+
+constexpr int NVARIANTS = 4;
+static int pick_variant(int64_t M, int64_t N, int64_t K) {
+    const char* e = getenv("TPL_GEMM_TILE");          // tuning / test override: one digit
+    if (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) return e[0] - '0';
+    static const int bm[NVARIANTS] = {256, 256, 128, 192}, bn[NVARIANTS] = {256, 192, 128, 192};
+    static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2};
+    static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576};
+    const double fixed_us = 12.0;
+    const int cus = compute_units();
+    const double nk = (double)((K + DK - 1) / DK);
+    int best = 0;
+    double best_c = 0;
+    for (int v = 0; v < NVARIANTS; ++v) {
+        int64_t tiles = ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]);
+        double per_cu = (double)((tiles + cus - 1) / cus);
+        double c = per_cu * nk * us_per_stage[v] + fixed_us * (wgs_per_cu[v] == 1 ? per_cu : 1.0);
+        if (v == 0 || c < best_c) { best = v; best_c = c; }
+    }
+    return best;
 }
 
 hipError_t gemm_bf16(const GemmArgs& a) {
@@ -362,15 +447,14 @@ hipError_t gemm_bf16(const GemmArgs& a) {
     p.lda = a.trans_a ? (int)a.M : (int)a.K;
     p.ldb = a.trans_b ? (int)a.K : (int)a.N;
     p.epi = a.epi;
-    p.tiles_m = (int)((a.M + DT - 1) / DT);
-    p.tiles_n = (int)((a.N + DT - 1) / DT);
+    p.tiles_m = p.tiles_n = 0;
     p.nk = (int)((a.K + DK - 1) / DK);
-    const int grid = p.tiles_m * p.tiles_n;
-    const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
-    if (a_kmaj && b_kmaj) return launch<true, true>(p, grid, a.stream);
-    if (a_kmaj && !b_kmaj) return launch<true, false>(p, grid, a.stream);
-    if (!a_kmaj && b_kmaj) return launch<false, true>(p, grid, a.stream);
-    return launch<false, false>(p, grid, a.stream);
+    switch (pick_variant(a.M, a.N, a.K)) {
+        case 1: return launch_layout<Tile<4, 3, 4>>(p, a);    // 256 x 192
+        case 2: return launch_layout<Tile<2, 2, 4>>(p, a);    // 128 x 128, two workgroups per CU
+        case 3: return launch_layout<Tile<3, 3, 3>>(p, a);    // 192 x 192, two workgroups per CU
+        default: return launch_layout<Tile<4, 4, 4>>(p, a);   // 256 x 256
+    }
 }
 
 }  // namespace tpl

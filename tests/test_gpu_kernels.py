@@ -23,12 +23,18 @@ GEMM_SHAPES = [(256, 256, 64), (520, 264, 136), (1000, 776, 2056), (64, 1536, 40
                (2048, 1536, 3080), (4104, 4360, 520)]
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+# bf16 runs once per tile variant of the MFMA kernel (forced through TPL_GEMM_TILE) and once with the
+# library's own choice; float has a single kernel.
+@pytest.mark.parametrize("dtype,tile", [("bf16", None), ("bf16", "0"), ("bf16", "1"), ("bf16", "2"), ("bf16", "3"), ("f32", None)])
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("epi", ["none", "bias", "bias_resid", "gelu", "dgelu"])
-def test_gemm_variants(dtype, ta, tb, epi):
+def test_gemm_variants(dtype, tile, ta, tb, epi, monkeypatch):
     import torch
     import paper_2111_05972_amd as pkg
+    if tile is None:
+        monkeypatch.delenv("TPL_GEMM_TILE", raising=False)
+    else:
+        monkeypatch.setenv("TPL_GEMM_TILE", tile)
     dt = pkg.TPL_BF16 if dtype == "bf16" else pkg.TPL_F32
     tol = 2e-2 if dtype == "bf16" else 1e-4
     for si, (M, N, K) in enumerate(GEMM_SHAPES):
