@@ -139,6 +139,36 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* params,
                  void* dx_attn_partial, void* dx_mlp_partial,
                  void* ws, size_t ws_bytes, void* hip_stream);
 
+/* Activation-checkpoint mode (App. H.2: activations are recomputed in backward instead of kept):
+ * backward without `saved`.  QKV, O, LSE, U and G are recomputed from x_attn, x_mlp into the front of
+ * `ws` (the two row-parallel forward GEMMs, whose outputs backward never reads, are not recomputed),
+ * then the backward of tp_layer_bwd runs.  Results are bit-identical to tp_layer_fwd + tp_layer_bwd.
+ * b_qkv and b_up must be set in `params`.  ws_bytes >= tp_layer_workspace_bytes_recompute(). */
+size_t tp_layer_workspace_bytes_recompute(const tp_layer_desc* desc);
+int tp_layer_bwd_recompute(const tp_layer_desc* desc, const tp_layer_params* params,
+                           const void* x_attn, const void* x_mlp,
+                           const void* dy_attn, const void* dy_mlp,
+                           const tp_layer_grads* grads,
+                           void* dx_attn_partial, void* dx_mlp_partial,
+                           void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Replicated layer normalisation either side of the shard.  In the speed-optimised distribution
+ * layer normalisation is not distributed (Sec. I.1): each rank normalises the whole [M, H] tensor.
+ *   z = a + b (b may be NULL: z = a);  y = (z - mean_H(z)) / sqrt(var_H(z) + eps) * gamma + beta
+ * (biased variance over the hidden dimension; eps is `layernorm_epsilon` of Sec. I.4).  Writes y, the
+ * per-row mean and 1/sqrt(var + eps) (float [M]) and, if z != NULL, the residual sum z.
+ * H must be a multiple of 8 and at most 16384.  a, b, z, y: [M, H] dtype; gamma, beta: [H] dtype. */
+int tp_layer_ln_fwd(int dtype, int64_t M, int64_t H, const void* a, const void* b,
+                    const void* gamma, const void* beta, float eps,
+                    void* z, void* y, float* mean, float* rstd, void* hip_stream);
+/* Backward: dz = rstd * (g - mean_H(g) - zh * mean_H(g * zh)), g = dy * gamma, zh = (z - mean) * rstd
+ * (dz is the gradient of both a and b); dgamma = sum_m dy * zh; dbeta = sum_m dy (fixed summation
+ * order).  z is the normalised input (what forward wrote to z, or a itself when b was NULL). */
+size_t tp_layer_ln_workspace_bytes(int64_t M, int64_t H);
+int tp_layer_ln_bwd(int dtype, int64_t M, int64_t H, const void* dy, const void* z,
+                    const float* mean, const float* rstd, const void* gamma,
+                    void* dz, void* dgamma, void* dbeta, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* One GEMM of the path with its fused epilogue, exposed for per-kernel tests and timing:
  *   C[M,N] = epi( opA(A) opB(B) ),  element type `dtype`, float accumulation.
  * trans_a == 0: A is [M,K] row-major, else A is [K,M] row-major (used as its transpose).

@@ -203,3 +203,30 @@ def max_rel_err(got, ref):
     den = np.abs(ref).max()
     num = np.abs(got - ref).max() if got.size else 0.0
     return float(num / den) if den > 0 else float(num)
+
+
+# ------------------------------------------------------------------------------------------------
+# Replicated LayerNorm around the shard (speed-optimised mode keeps layer normalisation undistributed,
+# Sec. I.1; epsilon and the pre/post placement are constructor arguments in Sec. I.4).  The normalised
+# tensor is the residual sum z = a + b (b optional); statistics are over the hidden dimension with the
+# biased variance, as in the usual definition of layer normalisation.
+# Pins: finite differences, zero-mean/unit-variance rows, shift invariance, PyTorch's F.layer_norm.
+# ------------------------------------------------------------------------------------------------
+def layernorm_fwd(a, b, gamma, beta, eps):
+    """z = a (+ b); y = (z - mean) / sqrt(var + eps) * gamma + beta.  Returns y, z, mean [M], rstd [M]."""
+    z = np.asarray(a, _F) + (0.0 if b is None else np.asarray(b, _F))
+    mean = z.mean(axis=1)
+    var = ((z - mean[:, None]) ** 2).mean(axis=1)
+    rstd = 1.0 / np.sqrt(var + _F(eps))
+    zh = (z - mean[:, None]) * rstd[:, None]
+    y = zh * np.asarray(gamma, _F) + np.asarray(beta, _F)
+    return y, z, mean, rstd
+
+
+def layernorm_bwd(dy, z, mean, rstd, gamma):
+    """Gradients of y w.r.t. z (the same for a and b), gamma and beta."""
+    dy, z, gamma = np.asarray(dy, _F), np.asarray(z, _F), np.asarray(gamma, _F)
+    zh = (z - np.asarray(mean, _F)[:, None]) * np.asarray(rstd, _F)[:, None]
+    g = dy * gamma
+    dz = (g - g.mean(axis=1, keepdims=True) - zh * (g * zh).mean(axis=1, keepdims=True)) * np.asarray(rstd, _F)[:, None]
+    return dz, (dy * zh).sum(axis=0), dy.sum(axis=0)

@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     tp_layer_validate, tp_layer_saved_bytes, tp_layer_saved_offsets, tp_layer_workspace_bytes,
     tp_layer_fwd, tp_layer_bwd, tp_layer_gemm, tp_layer_gemm_workspace_bytes,
     tp_layer_attn_fwd, tp_layer_attn_bwd, tp_layer_strerror, tp_layer_profile, tp_layer_profile_read,
+    tp_layer_workspace_bytes_recompute, tp_layer_bwd_recompute,
+    tp_layer_ln_workspace_bytes, tp_layer_ln_fwd, tp_layer_ln_bwd,
 )
 
 

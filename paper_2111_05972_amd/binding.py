@@ -72,6 +72,11 @@ def load_library():
         "tp_layer_gemm": (ci, [ci, ci, ci, i64, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp, ci, _vp, sz, _vp]),
         "tp_layer_attn_fwd": (ci, [ci, ci, ci, ci, ci, ci, _vp, _vp, _vp, _vp]),
         "tp_layer_attn_bwd": (ci, [ci, ci, ci, ci, ci, ci, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+        "tp_layer_workspace_bytes_recompute": (sz, [D]),
+        "tp_layer_bwd_recompute": (ci, [D, P, _vp, _vp, _vp, _vp, G, _vp, _vp, _vp, sz, _vp]),
+        "tp_layer_ln_workspace_bytes": (sz, [i64, i64]),
+        "tp_layer_ln_fwd": (ci, [ci, i64, i64, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _vp]),
+        "tp_layer_ln_bwd": (ci, [ci, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, sz, _vp]),
         "tp_layer_profile": (ci, [ci]),
         "tp_layer_profile_read": (ci, [ctypes.POINTER(ctypes.c_float), ci, ctypes.POINTER(ci)]),
         "tp_layer_strerror": (ctypes.c_char_p, [ci]),
@@ -165,6 +170,44 @@ def tp_layer_bwd(desc, params, x_attn, x_mlp, dy_attn, dy_mlp, saved, grads, dx_
         _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     if check and rc != TPL_OK:
         raise TpLayerError(rc, "tp_layer_bwd")
+    return rc
+
+
+def tp_layer_workspace_bytes_recompute(desc):
+    return load_library().tp_layer_workspace_bytes_recompute(ctypes.byref(desc))
+
+
+def tp_layer_bwd_recompute(desc, params, x_attn, x_mlp, dy_attn, dy_mlp, grads, dx_attn_partial,
+                           dx_mlp_partial, ws, ws_bytes=None, stream=None, check=True):
+    pr, gr = _params(params), _grads(grads)
+    rc = load_library().tp_layer_bwd_recompute(
+        ctypes.byref(desc), ctypes.byref(pr), _ptr(x_attn), _ptr(x_mlp), _ptr(dy_attn), _ptr(dy_mlp),
+        ctypes.byref(gr), _ptr(dx_attn_partial), _ptr(dx_mlp_partial), _ptr(ws),
+        _nbytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    if check and rc != TPL_OK:
+        raise TpLayerError(rc, "tp_layer_bwd_recompute")
+    return rc
+
+
+def tp_layer_ln_workspace_bytes(M, H):
+    return load_library().tp_layer_ln_workspace_bytes(M, H)
+
+
+def tp_layer_ln_fwd(dtype, M, H, a, b, gamma, beta, eps, z, y, mean, rstd, stream=None, check=True):
+    rc = load_library().tp_layer_ln_fwd(dtype, M, H, _ptr(a), _ptr(b), _ptr(gamma), _ptr(beta), float(eps),
+                                        _ptr(z), _ptr(y), _ptr(mean), _ptr(rstd), _stream(stream))
+    if check and rc != TPL_OK:
+        raise TpLayerError(rc, "tp_layer_ln_fwd")
+    return rc
+
+
+def tp_layer_ln_bwd(dtype, M, H, dy, z, mean, rstd, gamma, dz, dgamma, dbeta, ws, ws_bytes=None, stream=None,
+                    check=True):
+    rc = load_library().tp_layer_ln_bwd(dtype, M, H, _ptr(dy), _ptr(z), _ptr(mean), _ptr(rstd), _ptr(gamma),
+                                        _ptr(dz), _ptr(dgamma), _ptr(dbeta), _ptr(ws),
+                                        (_nbytes(ws) or 0) if ws_bytes is None else ws_bytes, _stream(stream))
+    if check and rc != TPL_OK:
+        raise TpLayerError(rc, "tp_layer_ln_bwd")
     return rc
 
 

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtp_layer.so")
-SOURCES = ["tp_layer.cpp", "simple_kernels.hip", "gemm_bf16.hip", "attn_bf16.hip"]
+SOURCES = ["tp_layer.cpp", "simple_kernels.hip", "gemm_bf16.hip", "attn_bf16.hip", "layernorm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-option-ignored"]

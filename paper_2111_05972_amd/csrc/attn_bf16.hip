@@ -37,8 +37,14 @@ constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LN2 = 0.69314718055994530942f;
 
 // ---- LDS tile of TILE rows x DH bf16, 16-byte chunks XOR-swizzled by row -------------------------
+// Two kinds of read hit these tiles: 16-byte reads of 16 consecutive rows at one chunk (operand with
+// the head dimension as K), and transposing 8-byte reads of 4 consecutive rows at two neighbouring
+// 32-byte column groups.  The XOR below makes both conflict-free over the 64 banks (256 bytes): the
+// bits that separate the 4 rows of a transposing read move the 64-byte column group, the remaining
+// row bits move the chunk inside it.
 template <int DH> __device__ __forceinline__ int swz(int row) {
-    return DH == 64 ? ((row >> 1) & 7) : (row & 15);
+    return DH == 64 ? ((((row >> 1) & 1) << 2) | ((row >> 2) & 3))     // 128-byte rows, 8 chunks
+                    : (((row & 3) << 2) | ((row >> 2) & 3));           // 256-byte rows, 16 chunks
 }
 template <int DH> constexpr int tile_bytes() { return TILE * DH * 2; }
 template <int DH> constexpr int chunks_per_thread() { return TILE * DH / 8 / ATHREADS; }
@@ -118,6 +124,8 @@ __device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, flo
     o[0] = (bf16_t)a; o[1] = (bf16_t)b; o[2] = (bf16_t)c; o[3] = (bf16_t)d;
     *reinterpret_cast<bf16x4*>(p) = o;
 }
+// 2^x on the hardware transcendental unit (arguments here are <= ~0; results below 2^-126 flush to 0).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
 // =================================================================================================
@@ -176,27 +184,33 @@ __global__ __launch_bounds__(ATHREADS) void attn_fwd_kernel(const bf16_t* __rest
             f32x16 s = zero16();
 #pragma unroll
             for (int ks = 0; ks < DH / 16; ++ks) s = MFMA(frag_k<DH>(ks_, sb * 32, ks, lane), qf[ks], s);
-            float mb = -INFINITY;
+            // masking is needed only in tiles that straddle the diagonal or the end of the sequence
+            if (kv0 + 31 >= S || (CAUSAL && kv0 + 31 > q0)) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int kv = kv0 + (v >> 2) * 8 + half * 4 + (v & 3);
-                bool ok = kv < S && (!CAUSAL || kv <= q);
-                s[v] = ok ? s[v] * c2 : -INFINITY;
-                mb = fmaxf(mb, s[v]);
+                for (int v = 0; v < 16; ++v) {
+                    int kv = kv0 + (v >> 2) * 8 + half * 4 + (v & 3);
+                    bool ok = kv < S && (!CAUSAL || kv <= q);
+                    s[v] = ok ? s[v] : -INFINITY;
+                }
             }
-            mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
+            float mb = s[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mb = fmaxf(mb, s[v]);
+            mb = fmaxf(mb, __shfl_xor(mb, 32, 64)) * c2;      // c2 > 0: scaling commutes with max
             float mn = fmaxf(m, mb);
             float mu = mn == -INFINITY ? 0.0f : mn;
-            float alpha = exp2f(m - mu);
+            float alpha = fast_exp2(m - mu);
             m = mn;
             float ps = 0.0f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { s[v] = exp2f(s[v] - mu); ps += s[v]; }
+            for (int v = 0; v < 16; ++v) { s[v] = fast_exp2(fmaf(s[v], c2, -mu)); ps += s[v]; }
             lsum = lsum * alpha + ps;
+            if (__any(alpha != 1.0f)) {                       // the running maximum rarely moves
 #pragma unroll
-            for (int dt = 0; dt < DH / 32; ++dt)
+                for (int dt = 0; dt < DH / 32; ++dt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+                    for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+            }
             bf16x8 pb0 = pack_regs(s, 0), pb1 = pack_regs(s, 8);
 #pragma unroll
             for (int dt = 0; dt < DH / 32; ++dt) {
@@ -334,6 +348,7 @@ __global__ __launch_bounds__(ATHREADS) void attn_dkv_kernel(const bf16_t* __rest
                 s = MFMA(frag_k<DH>(qs, sb * 32, ks, lane), kf[ks], s);
                 dp = MFMA(frag_k<DH>(dos, sb * 32, ks, lane), vf[ks], dp);
             }
+            const bool need_mask = qs0 + 31 >= S || k0 + 31 >= S || (CAUSAL && k0 + 31 > qs0);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float4 l4 = *reinterpret_cast<const float4*>(ls + sb * 32 + 8 * i + 4 * half);
@@ -342,9 +357,12 @@ __global__ __launch_bounds__(ATHREADS) void attn_dkv_kernel(const bf16_t* __rest
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     int v = 4 * i + j;
-                    int qi = qs0 + 8 * i + 4 * half + j;
-                    bool ok = qi < S && kv < S && (!CAUSAL || kv <= qi);
-                    float p = ok ? exp2f(s[v] * c2 - lv[j]) : 0.0f;
+                    float p = fast_exp2(fmaf(s[v], c2, -lv[j]));
+                    if (need_mask) {
+                        int qi = qs0 + 8 * i + 4 * half + j;
+                        bool ok = qi < S && kv < S && (!CAUSAL || kv <= qi);
+                        p = ok ? p : 0.0f;
+                    }
                     s[v] = p;
                     dp[v] = p * (dp[v] - dvv[j]);
                 }
@@ -443,11 +461,15 @@ __global__ __launch_bounds__(ATHREADS) void attn_dq_kernel(const bf16_t* __restr
                 s = MFMA(frag_k<DH>(ks_, sb * 32, ks, lane), qf[ks], s);
                 dp = MFMA(frag_k<DH>(vs_, sb * 32, ks, lane), dof[ks], dp);
             }
+            const bool need_mask = q0 + 31 >= S || kv0 + 31 >= S || (CAUSAL && kv0 + 31 > q0);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                int kv = kv0 + (v >> 2) * 8 + half * 4 + (v & 3);
-                bool ok = q < S && kv < S && (!CAUSAL || kv <= q);
-                float p = ok ? exp2f(s[v] * c2 - l2) : 0.0f;
+                float p = fast_exp2(fmaf(s[v], c2, -l2));
+                if (need_mask) {
+                    int kv = kv0 + (v >> 2) * 8 + half * 4 + (v & 3);
+                    bool ok = q < S && kv < S && (!CAUSAL || kv <= q);
+                    p = ok ? p : 0.0f;
+                }
                 dp[v] = p * (dp[v] - dq_d);
             }
             bf16x8 g0 = pack_regs(dp, 0), g1 = pack_regs(dp, 8);

@@ -46,6 +46,28 @@ hipError_t attn_simple_bwd(const AttnArgs& a);
 // out[n] = sum_m X[m,n]  (bias gradients), deterministic.
 hipError_t colsum(int dtype, int64_t M, int64_t N, const void* X, void* out, float* scratch, hipStream_t s);
 size_t colsum_scratch_bytes(int64_t M, int64_t N);
+// out[n] = sum over slabs of part[slab * stride + n], in slab order.
+hipError_t sum_partials_strided(int dtype, int64_t slabs, int64_t N, const float* part, int64_t stride,
+                                void* out, hipStream_t s);
+
+// LayerNorm over the hidden dimension of z = a (+ b): HBM-bound, one pass over each tensor.
+struct LnArgs {
+    int dtype;
+    int64_t M, H;
+    const void* a; const void* b;          // b may be null
+    const void* gamma; const void* beta;
+    float eps;
+    void* z;                               // fwd: a + b written here if non-null; bwd: the normalised input
+    void* y;
+    float* mean; float* rstd;              // [M]
+    const void* dy; void* dz; void* dgamma; void* dbeta;   // bwd
+    float* partials;                       // bwd scratch: ln_partial_rows(M) x 2 x H floats
+    hipStream_t stream;
+};
+bool ln_supported(int64_t H);
+int64_t ln_partial_rows(int64_t M);
+hipError_t ln_fwd(const LnArgs& a);
+hipError_t ln_bwd(const LnArgs& a);
 
 // bf16 MFMA kernels for gfx950.
 bool gemm_bf16_supported(const GemmArgs& a);

@@ -326,30 +326,49 @@ hipError_t attn_simple_bwd(const AttnArgs& a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Column sums (bias gradients): out[n] = sum_m X[m,n].  Two fixed-order stages so results do not
-// depend on scheduling: each block sums a slab of CS_ROWS rows into scratch[slab][n], then one
-// thread per column adds the slabs in order.
+// Column sums (bias gradients): out[n] = sum_m X[m,n].  HBM-bound: X is read once with 16-byte loads.
+// Two fixed-order stages so results do not depend on scheduling: a block sums a slab of CS_ROWS rows
+// for 512 columns (64 column groups of 8 x 4 row lanes, combined through LDS in lane order) into
+// scratch[slab][n]; then one thread per column adds the slabs in order.
 // ------------------------------------------------------------------------------------------------
-constexpr int CS_ROWS = 128;
+constexpr int CS_ROWS = 64;
 
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_stage1(int64_t M, int64_t N, const T* __restrict__ X,
                                                      float* __restrict__ part) {
-    int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (n >= N) return;
-    int64_t m0 = (int64_t)blockIdx.y * CS_ROWS, m1 = m0 + CS_ROWS < M ? m0 + CS_ROWS : M;
-    float s = 0.0f;
-    for (int64_t m = m0; m < m1; ++m) s += to_f32(X[m * N + n]);
-    part[(int64_t)blockIdx.y * N + n] = s;
+    __shared__ float red[4][64][8];
+    const int cg = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const int64_t n = ((int64_t)blockIdx.x * 64 + cg) * 8;
+    const int64_t m0 = (int64_t)blockIdx.y * CS_ROWS, m1 = m0 + CS_ROWS < M ? m0 + CS_ROWS : M;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const int cnt = n + 8 <= N ? 8 : (n < N ? (int)(N - n) : 0);     // columns this thread owns
+    if (cnt == 8) {
+        for (int64_t m = m0 + rl; m < m1; m += 4) {
+            float v[8];
+            load8(X + m * N + n, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += v[e];
+        }
+    } else if (cnt > 0) {                                            // ragged tail of a float matrix
+        for (int64_t m = m0 + rl; m < m1; m += 4)
+            for (int e = 0; e < cnt; ++e) acc[e] += to_f32(X[m * N + n + e]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[rl][cg][e] = acc[e];
+    __syncthreads();
+    if (rl == 0) {
+        float* dst = part + (int64_t)blockIdx.y * N + n;
+        for (int e = 0; e < cnt; ++e) dst[e] = ((red[0][cg][e] + red[1][cg][e]) + red[2][cg][e]) + red[3][cg][e];
+    }
 }
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_stage2(int64_t slabs, int64_t N,
+__global__ __launch_bounds__(256) void colsum_stage2(int64_t slabs, int64_t N, int64_t stride,
                                                      const float* __restrict__ part,
                                                      T* __restrict__ out) {
     int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (n >= N) return;
     float s = 0.0f;
-    for (int64_t i = 0; i < slabs; ++i) s += part[i * N + n];
+    for (int64_t i = 0; i < slabs; ++i) s += part[i * stride + n];
     out[n] = from_f32<T>(s);
 }
 
@@ -357,16 +376,24 @@ size_t colsum_scratch_bytes(int64_t M, int64_t N) {
     return (size_t)((M + CS_ROWS - 1) / CS_ROWS) * (size_t)N * sizeof(float);
 }
 
+hipError_t sum_partials_strided(int dtype, int64_t slabs, int64_t N, const float* part, int64_t stride,
+                                void* out, hipStream_t s) {
+    dim3 g2((unsigned)((N + 255) / 256));
+    if (dtype == F32) hipLaunchKernelGGL(colsum_stage2<float>, g2, dim3(256), 0, s, slabs, N, stride, part, (float*)out);
+    else hipLaunchKernelGGL(colsum_stage2<bf16_t>, g2, dim3(256), 0, s, slabs, N, stride, part, (bf16_t*)out);
+    return hipGetLastError();
+}
+
 hipError_t colsum(int dtype, int64_t M, int64_t N, const void* X, void* out, float* scratch,
                   hipStream_t s) {
     int64_t slabs = (M + CS_ROWS - 1) / CS_ROWS;
-    dim3 g1((unsigned)((N + 255) / 256), (unsigned)slabs), g2((unsigned)((N + 255) / 256));
+    dim3 g1((unsigned)((N + 511) / 512), (unsigned)slabs), g2((unsigned)((N + 255) / 256));
     if (dtype == F32) {
         hipLaunchKernelGGL(colsum_stage1<float>, g1, dim3(256), 0, s, M, N, (const float*)X, scratch);
-        hipLaunchKernelGGL(colsum_stage2<float>, g2, dim3(256), 0, s, slabs, N, scratch, (float*)out);
+        hipLaunchKernelGGL(colsum_stage2<float>, g2, dim3(256), 0, s, slabs, N, N, scratch, (float*)out);
     } else {
         hipLaunchKernelGGL(colsum_stage1<bf16_t>, g1, dim3(256), 0, s, M, N, (const bf16_t*)X, scratch);
-        hipLaunchKernelGGL(colsum_stage2<bf16_t>, g2, dim3(256), 0, s, slabs, N, scratch, (bf16_t*)out);
+        hipLaunchKernelGGL(colsum_stage2<bf16_t>, g2, dim3(256), 0, s, slabs, N, N, scratch, (bf16_t*)out);
     }
     return hipGetLastError();
 }

@@ -142,6 +142,43 @@ GemmArgs mk(const Dims& x, int ta, int tb, int64_t M, int64_t N, int64_t K, cons
     return g;
 }
 
+// Forward kernels in order.  With row_parallel == false the two row-parallel GEMMs (whose outputs the
+// backward pass never reads) are skipped: that is the recomputation done in checkpoint mode.
+int fwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const void* x_mlp, void* y_attn,
+             void* y_mlp, void* saved, void* ws, size_t ws_bytes, hipStream_t s, bool row_parallel) {
+    int rc;
+    tp_layer_saved_layout L;
+    saved_layout(x, &L);
+    char* sv = (char*)saved;
+    void *qkv = sv + L.qkv, *o = sv + L.o, *u = sv + L.u, *g = sv + L.g;
+    float* lse = (float*)(sv + L.lse);
+    GemmScratch sc{ws, ws_bytes, s};
+
+    // attention block: column-parallel fused QKV, attention on the local heads, row-parallel out-proj
+    GemmArgs g1 = mk(x, 0, 0, x.M, 3 * x.Hl, x.H, x_attn, p->w_qkv, qkv, sc);
+    g1.bias = p->b_qkv;
+    if ((rc = run_gemm(g1))) return rc;
+    AttnArgs at{};
+    at.dtype = x.dtype; at.B = (int)x.B; at.S = (int)x.S; at.nl = (int)x.nl; at.dh = (int)x.dh;
+    at.causal = x.causal; at.qkv = qkv; at.o = o; at.lse = lse; at.stream = s;
+    if ((rc = run_attn(at, false))) return rc;
+    if (row_parallel) {
+        GemmArgs g3 = mk(x, 0, 0, x.M, x.H, x.Hl, o, p->w_o, y_attn, sc);
+        if (x.row_epi) { g3.bias = p->b_o; g3.resid = x_attn; }
+        if ((rc = run_gemm(g3))) return rc;
+    }
+    // MLP block: column-parallel up-projection + GeLU, row-parallel down-projection
+    GemmArgs g4 = mk(x, 0, 0, x.M, x.Il, x.H, x_mlp, p->w_up, g, sc);
+    g4.bias = p->b_up; g4.aux = u; g4.epi = EPI_GELU;
+    if ((rc = run_gemm(g4))) return rc;
+    if (row_parallel) {
+        GemmArgs g5 = mk(x, 0, 0, x.M, x.H, x.Il, g, p->w_dn, y_mlp, sc);
+        if (x.row_epi) { g5.bias = p->b_dn; g5.resid = x_mlp; }
+        if ((rc = run_gemm(g5))) return rc;
+    }
+    return TPL_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -187,32 +224,7 @@ int tp_layer_fwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
                           p->b_o, p->w_up, p->b_up, p->w_dn, p->b_dn};
     for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
     if (ws_bytes < fwd_gemm_ws(x)) return TPL_EWORKSPACE;
-    hipStream_t s = (hipStream_t)hip_stream;
-    tp_layer_saved_layout L;
-    saved_layout(x, &L);
-    char* sv = (char*)saved;
-    void *qkv = sv + L.qkv, *o = sv + L.o, *u = sv + L.u, *g = sv + L.g;
-    float* lse = (float*)(sv + L.lse);
-    GemmScratch sc{ws, ws_bytes, s};
-
-    // attention block: column-parallel fused QKV, attention on the local heads, row-parallel out-proj
-    GemmArgs g1 = mk(x, 0, 0, x.M, 3 * x.Hl, x.H, x_attn, p->w_qkv, qkv, sc);
-    g1.bias = p->b_qkv;
-    if ((rc = run_gemm(g1))) return rc;
-    AttnArgs at{};
-    at.dtype = x.dtype; at.B = (int)x.B; at.S = (int)x.S; at.nl = (int)x.nl; at.dh = (int)x.dh;
-    at.causal = x.causal; at.qkv = qkv; at.o = o; at.lse = lse; at.stream = s;
-    if ((rc = run_attn(at, false))) return rc;
-    GemmArgs g3 = mk(x, 0, 0, x.M, x.H, x.Hl, o, p->w_o, y_attn, sc);
-    if (x.row_epi) { g3.bias = p->b_o; g3.resid = x_attn; }
-    if ((rc = run_gemm(g3))) return rc;
-    // MLP block: column-parallel up-projection + GeLU, row-parallel down-projection
-    GemmArgs g4 = mk(x, 0, 0, x.M, x.Il, x.H, x_mlp, p->w_up, g, sc);
-    g4.bias = p->b_up; g4.aux = u; g4.epi = EPI_GELU;
-    if ((rc = run_gemm(g4))) return rc;
-    GemmArgs g5 = mk(x, 0, 0, x.M, x.H, x.Il, g, p->w_dn, y_mlp, sc);
-    if (x.row_epi) { g5.bias = p->b_dn; g5.resid = x_mlp; }
-    return run_gemm(g5);
+    return fwd_impl(x, p, x_attn, x_mlp, y_attn, y_mlp, saved, ws, ws_bytes, (hipStream_t)hip_stream, true);
 }
 
 int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void* x_attn,
@@ -277,6 +289,81 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, sc);
     if (x.row_epi) d1.resid = dy_attn;
     return run_gemm(d1);
+}
+
+size_t tp_layer_workspace_bytes_recompute(const tp_layer_desc* desc) {
+    Dims x;
+    if (resolve(desc, &x) != TPL_OK) return 0;
+    tp_layer_saved_layout L;
+    saved_layout(x, &L);
+    BwdWs W;
+    bwd_layout(x, &W);
+    return up(L.total) + W.total;
+}
+
+int tp_layer_bwd_recompute(const tp_layer_desc* desc, const tp_layer_params* p, const void* x_attn,
+                           const void* x_mlp, const void* dy_attn, const void* dy_mlp,
+                           const tp_layer_grads* gr, void* dx_attn, void* dx_mlp, void* ws, size_t ws_bytes,
+                           void* hip_stream) {
+    Dims x;
+    int rc = resolve(desc, &x);
+    if (rc != TPL_OK) return rc;
+    if (!p || !x_attn || !x_mlp || !ws) return TPL_EINVAL;
+    if (!p->w_qkv || !p->b_qkv || !p->w_o || !p->w_up || !p->b_up || !p->w_dn) return TPL_EINVAL;
+    const void* ptrs[] = {x_attn, x_mlp, ws, p->w_qkv, p->b_qkv, p->w_o, p->w_up, p->b_up, p->w_dn};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    if (ws_bytes < tp_layer_workspace_bytes_recompute(desc)) return TPL_EWORKSPACE;
+    tp_layer_saved_layout L;
+    saved_layout(x, &L);
+    char* saved = (char*)ws;
+    char* rest = saved + up(L.total);
+    const size_t rest_bytes = ws_bytes - up(L.total);
+    // recompute QKV, O, LSE, U, G from the block inputs, then the ordinary backward
+    rc = fwd_impl(x, p, x_attn, x_mlp, nullptr, nullptr, saved, rest, rest_bytes, (hipStream_t)hip_stream, false);
+    if (rc != TPL_OK) return rc;
+    return tp_layer_bwd(desc, p, x_attn, x_mlp, dy_attn, dy_mlp, saved, gr, dx_attn, dx_mlp, rest, rest_bytes,
+                        hip_stream);
+}
+
+static int ln_check(int dtype, int64_t M, int64_t H) {
+    if (dtype != TPL_F32 && dtype != TPL_BF16) return TPL_EINVAL;
+    if (M <= 0 || H <= 0) return TPL_EINVAL;
+    if (!ln_supported(H)) return TPL_EUNSUPPORTED;
+    return TPL_OK;
+}
+
+size_t tp_layer_ln_workspace_bytes(int64_t M, int64_t H) {
+    if (M <= 0 || H <= 0) return 0;
+    return up((size_t)ln_partial_rows(M) * 2 * (size_t)H * sizeof(float));
+}
+
+int tp_layer_ln_fwd(int dtype, int64_t M, int64_t H, const void* a, const void* b, const void* gamma,
+                    const void* beta, float eps, void* z, void* y, float* mean, float* rstd, void* hip_stream) {
+    int rc = ln_check(dtype, M, H);
+    if (rc) return rc;
+    if (!a || !gamma || !beta || !y || !mean || !rstd || !(eps >= 0.0f)) return TPL_EINVAL;
+    const void* ptrs[] = {a, b, gamma, beta, z, y, mean, rstd};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    LnArgs l{};
+    l.dtype = dtype; l.M = M; l.H = H; l.a = a; l.b = b; l.gamma = gamma; l.beta = beta; l.eps = eps;
+    l.z = z; l.y = y; l.mean = mean; l.rstd = rstd; l.stream = (hipStream_t)hip_stream;
+    return ln_fwd(l) == hipSuccess ? TPL_OK : TPL_EHIP;
+}
+
+int tp_layer_ln_bwd(int dtype, int64_t M, int64_t H, const void* dy, const void* z, const float* mean,
+                    const float* rstd, const void* gamma, void* dz, void* dgamma, void* dbeta, void* ws,
+                    size_t ws_bytes, void* hip_stream) {
+    int rc = ln_check(dtype, M, H);
+    if (rc) return rc;
+    if (!dy || !z || !mean || !rstd || !gamma || !dz || !dgamma || !dbeta || !ws) return TPL_EINVAL;
+    const void* ptrs[] = {dy, z, mean, rstd, gamma, dz, dgamma, dbeta, ws};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    if (ws_bytes < tp_layer_ln_workspace_bytes(M, H)) return TPL_EWORKSPACE;
+    LnArgs l{};
+    l.dtype = dtype; l.M = M; l.H = H; l.dy = dy; l.z = const_cast<void*>(z); l.mean = const_cast<float*>(mean);
+    l.rstd = const_cast<float*>(rstd); l.gamma = gamma; l.dz = dz; l.dgamma = dgamma; l.dbeta = dbeta;
+    l.partials = (float*)ws; l.stream = (hipStream_t)hip_stream;
+    return ln_bwd(l) == hipSuccess ? TPL_OK : TPL_EHIP;
 }
 
 size_t tp_layer_gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K) {

@@ -1,0 +1,115 @@
+"""GPU parity for the rows next to the hot path: replicated LayerNorm (forward, backward) against the
+oracle, and the activation-checkpoint backward, which must reproduce tp_layer_fwd + tp_layer_bwd exactly."""
+import numpy as np
+import pytest
+
+import oracle
+import synthetic
+from synthetic.configs import small_variant
+
+from gpu_util import compare, gpu_outputs, oracle_outputs, shard_inputs
+
+pytestmark = pytest.mark.gpu
+
+LN_CASES = [(7, 264), (300, 1024), (64, 4096), (33, 12288), (5, 16384), (2048, 1024), (1, 8)]
+
+
+def _draw(seed, shape, sigma, dtype, mean=0.0):
+    n = int(np.prod(shape))
+    return synthetic.quantize(synthetic.normal(seed, n, sigma) + np.float32(mean), dtype).reshape(shape)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("with_b", [True, False])
+def test_layernorm_fwd_bwd(dtype, with_b):
+    import torch
+    import paper_2111_05972_amd as pkg
+    dt = pkg.TPL_BF16 if dtype == "bf16" else pkg.TPL_F32
+    tol = 2e-2 if dtype == "bf16" else 1e-4
+    eps = 1e-5
+    st = torch.cuda.current_stream()
+    for ci, (M, H) in enumerate(LN_CASES):
+        print(f"\n[ln] {dtype} with_b={with_b} M={M} H={H}", flush=True)
+        a = _draw(900 + ci, (M, H), 1.0, dtype, mean=0.5)
+        b = _draw(910 + ci, (M, H), 1.0, dtype) if with_b else None
+        gamma = _draw(920 + ci, (H,), 0.2, dtype, mean=1.0)
+        beta = _draw(930 + ci, (H,), 0.2, dtype)
+        dy = _draw(940 + ci, (M, H), 1.0, dtype)
+        y_ref, z_ref, mean_ref, rstd_ref = oracle.layernorm_fwd(a, b, gamma, beta, eps)
+        T = lambda v: pkg.to_device(v, dt)  # noqa: E731
+        a_d, g_d, be_d, dy_d = T(a), T(gamma), T(beta), T(dy)
+        b_d = T(b) if with_b else None
+        z_d = torch.empty_like(a_d) if with_b else None
+        y_d = torch.empty_like(a_d)
+        mean_d = torch.empty(M, dtype=torch.float32, device="cuda")
+        rstd_d = torch.empty_like(mean_d)
+        pkg.tp_layer_ln_fwd(dt, M, H, a_d, b_d, g_d, be_d, eps, z_d, y_d, mean_d, rstd_d, stream=st)
+        torch.cuda.synchronize()
+        assert oracle.max_rel_err(y_d.float().cpu().numpy(), y_ref) <= tol
+        assert oracle.max_rel_err(mean_d.cpu().numpy(), mean_ref) <= tol
+        assert oracle.max_rel_err(rstd_d.cpu().numpy(), rstd_ref) <= tol
+        if with_b:
+            assert oracle.max_rel_err(z_d.float().cpu().numpy(), z_ref) <= tol
+        # backward takes the stored z and the stored statistics, as a training step would
+        zin = z_d if with_b else a_d
+        dz_ref, dg_ref, db_ref = oracle.layernorm_bwd(dy, z_ref, mean_ref, rstd_ref, gamma)
+        dz_d = torch.empty_like(a_d)
+        dg_d, db_d = torch.empty_like(g_d), torch.empty_like(g_d)
+        ws = torch.empty(pkg.tp_layer_ln_workspace_bytes(M, H), dtype=torch.uint8, device="cuda")
+        pkg.tp_layer_ln_bwd(dt, M, H, dy_d, zin, mean_d, rstd_d, g_d, dz_d, dg_d, db_d, ws, stream=st)
+        torch.cuda.synchronize()
+        assert oracle.max_rel_err(dz_d.float().cpu().numpy(), dz_ref) <= tol, (M, H)
+        assert oracle.max_rel_err(dg_d.float().cpu().numpy(), dg_ref) <= tol, (M, H)
+        assert oracle.max_rel_err(db_d.float().cpu().numpy(), db_ref) <= tol, (M, H)
+        # run-to-run identical
+        dg2 = torch.empty_like(dg_d)
+        pkg.tp_layer_ln_bwd(dt, M, H, dy_d, zin, mean_d, rstd_d, g_d, dz_d, dg2, db_d, ws, stream=st)
+        torch.cuda.synchronize()
+        assert torch.equal(dg2, dg_d)
+
+
+def test_layernorm_rejects_unsupported_widths():
+    import paper_2111_05972_amd as pkg
+    ok = 0x1000
+    assert pkg.tp_layer_ln_fwd(pkg.TPL_BF16, 4, 16392, ok, None, ok, ok, 1e-5, None, ok, ok, ok, check=False) == pkg.TPL_EUNSUPPORTED
+    assert pkg.tp_layer_ln_fwd(pkg.TPL_BF16, 4, 12, ok, None, ok, ok, 1e-5, None, ok, ok, ok, check=False) == pkg.TPL_EUNSUPPORTED
+    assert pkg.tp_layer_ln_fwd(pkg.TPL_BF16, 0, 16, ok, None, ok, ok, 1e-5, None, ok, ok, ok, check=False) == pkg.TPL_EINVAL
+    assert pkg.tp_layer_ln_bwd(pkg.TPL_BF16, 4, 16, ok, ok, ok, ok, ok, ok, ok, ok, ok, ws_bytes=8, check=False) == pkg.TPL_EWORKSPACE
+
+
+CKPT_CASES = [
+    small_variant(synthetic.CONFIGS[2], name="ckpt-bf16", hidden=768, heads=12, head_dim=64, intermediate=3072,
+                  tp_degree=2, tp_rank=1, seq=320, micro_batch=2, causal=True, row_epilogue=True),
+    small_variant(synthetic.CONFIGS[1], name="ckpt-f32", hidden=128, heads=2, head_dim=64, intermediate=512,
+                  tp_degree=1, tp_rank=0, seq=70, micro_batch=2, causal=False, row_epilogue=False),
+    synthetic.CONFIGS[5],
+]
+
+
+@pytest.mark.parametrize("cfg", CKPT_CASES, ids=[c.name for c in CKPT_CASES])
+def test_checkpoint_backward_reproduces_saved_backward(cfg):
+    import torch
+    import paper_2111_05972_amd as pkg
+    print(f"\n[ckpt] {cfg.name}", flush=True)
+    d, sh = shard_inputs(cfg)
+    base = gpu_outputs(cfg, d, sh)
+    dt = pkg.TPL_F32 if cfg.dtype == "f32" else pkg.TPL_BF16
+    layer = pkg.TpLayer(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt,
+                        cfg.causal, cfg.row_epilogue, cfg.head_dim, cfg.intermediate)
+    p = {k: pkg.to_device(v, dt) for k, v in sh.items()}
+    x = {k: pkg.to_device(d[k], dt) for k in ("x_a", "x_m", "dy_a", "dy_m")}
+    grads = layer.empty_grads()
+    dx_a, dx_m = layer.empty_outputs()
+    ws = torch.empty(pkg.tp_layer_workspace_bytes_recompute(layer.desc), dtype=torch.uint8, device="cuda")
+    pkg.tp_layer_bwd_recompute(layer.desc, p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m, ws,
+                               stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    got = {"dx_a": dx_a, "dx_m": dx_m, **grads}
+    for k, v in got.items():
+        if k in base:
+            assert np.array_equal(v.float().cpu().numpy(), base[k]), k
+    if cfg.cfg_id != 5 or True:
+        ref = oracle_outputs(cfg, d, sh)
+        full = dict(base)
+        full.update({k: v.float().cpu().numpy() for k, v in got.items() if k in base})
+        compare(cfg, full, ref)
