@@ -32,6 +32,70 @@ def gemm_list(cfg):
     ]
 
 
+def bench_layernorm(args, cfg, dt, pkg, torch, synthetic):
+    """Replicated LayerNorm (forward with residual add, then backward) on the config's [M, H] activation."""
+    M, H = cfg.tokens, cfg.hidden
+    es = 4 if cfg.dtype == "f32" else 2
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    mk = lambda seed, shape, sigma, mean=0.0: pkg.to_device(  # noqa: E731
+        synthetic.quantize(synthetic.normal(seed, int(__import__("numpy").prod(shape)), sigma) + mean, cfg.dtype).reshape(shape), dt)
+    a, b, dy = mk(1, (M, H), 1.0), mk(2, (M, H), 1.0), mk(3, (M, H), 1.0)
+    gamma, beta = mk(4, (H,), 0.1, 1.0), mk(5, (H,), 0.1)
+    z, y, dz = (torch.empty(M, H, dtype=tdt, device="cuda") for _ in range(3))
+    dg, db = torch.empty_like(gamma), torch.empty_like(gamma)
+    mean = torch.empty(M, dtype=torch.float32, device="cuda")
+    rstd = torch.empty_like(mean)
+    ws = torch.empty(pkg.tp_layer_ln_workspace_bytes(M, H), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def fwd():
+        pkg.tp_layer_ln_fwd(dt, M, H, a, b, gamma, beta, 1e-5, z, y, mean, rstd, stream=stream)
+
+    def bwd():
+        pkg.tp_layer_ln_bwd(dt, M, H, dy, z, mean, rstd, gamma, dz, dg, db, ws, stream=stream)
+
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(n):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / n
+    for _ in range(args.warmup):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t1) / args.steps
+    fwd_ms, bwd_ms = timed(fwd, args.steps), timed(bwd, args.steps)
+    fwd_bytes, bwd_bytes = 4.0 * M * H * es, 3.0 * M * H * es        # a, b -> z, y ; dy, z -> dz
+    import oracle
+    import numpy as np
+    c0 = time.perf_counter()
+    an, bn, gn, ben, dyn = (v.float().cpu().numpy() for v in (a, b, gamma, beta, dy))
+    yr, zr, mr, rr = oracle.layernorm_fwd(an, bn, gn, ben, 1e-5)
+    dzr, dgr, dbr = oracle.layernorm_bwd(dyn, zr, mr, rr, gn)
+    cpu_s = time.perf_counter() - c0
+    err = max(oracle.max_rel_err(y.float().cpu().numpy(), yr), oracle.max_rel_err(dz.float().cpu().numpy(), dzr),
+              oracle.max_rel_err(dg.float().cpu().numpy(), dgr), oracle.max_rel_err(db.float().cpu().numpy(), dbr))
+    gbs = (fwd_bytes + bwd_bytes) / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "GB/s of algorithmic HBM bytes, replicated LayerNorm fwd+bwd", "value": round(gbs, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"LayerNorm on [M={M}, H={H}] of config {cfg.cfg_id}: {cfg.name}"},
+        "roofline": {"kernel": "ln_fwd_kernel + ln_bwd_kernel", "bound": "hbm",
+                     "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbs / 8000.0, 4),
+                     "traffic": None, "fwd": {"ms": round(fwd_ms, 4), "GBps": round(fwd_bytes / fwd_ms / 1e6, 1)},
+                     "bwd": {"ms": round(bwd_ms, 4), "GBps": round(bwd_bytes / bwd_ms / 1e6, 1)}},
+        "cpu_baseline": {"value": round((fwd_bytes + bwd_bytes) / cpu_s / 1e9, 2), "unit": "GB/s", "cores": os.cpu_count(),
+                         "kind": "oracle", "sample": "full workload, one fwd+bwd pass", "seconds": round(cpu_s, 2)},
+        "max_rel_err_vs_oracle": err}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,6 +104,9 @@ def main():
     ap.add_argument("--config", default="5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "ln"],
+                    help="layer: tp_layer_fwd + tp_layer_bwd (the headline metric); layer-checkpoint: tp_layer_fwd + "
+                         "tp_layer_bwd_recompute; ln: replicated LayerNorm forward + backward on the config's [M, H]")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -67,6 +134,8 @@ def main():
     cfg = synthetic.get_config(key)
     dt = pkg.TPL_F32 if cfg.dtype == "f32" else pkg.TPL_BF16
     peak = F32_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_PEAK_TFLOPS
+    if args.workload == "ln":
+        return bench_layernorm(args, cfg, dt, pkg, torch, synthetic)
 
     t0 = time.time()
     d = synthetic.make_inputs(cfg)
@@ -82,9 +151,17 @@ def main():
     stream = torch.cuda.current_stream()
     gen_s = time.time() - t0
 
+    ckpt = args.workload == "layer-checkpoint"
+    ws_ckpt = torch.empty(pkg.tp_layer_workspace_bytes_recompute(layer.desc), dtype=torch.uint8,
+                          device="cuda") if ckpt else None
+
     def step():
         layer.forward(p, x["x_a"], x["x_m"], y_a, y_m, stream=stream)
-        layer.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m, stream=stream)
+        if ckpt:    # backward recomputes QKV, O, LSE, U, G from the block inputs instead of reading `saved`
+            pkg.tp_layer_bwd_recompute(layer.desc, p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m,
+                                       ws_ckpt, stream=stream)
+        else:
+            layer.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m, stream=stream)
 
     for _ in range(args.warmup):
         step()
@@ -126,8 +203,16 @@ def main():
         torch.cuda.synchronize()
         ms = pkg.tp_layer_profile_read()
         pkg.tp_layer_profile(0)
-        assert len(ms) == 12 * reps, len(ms)
-        per = {n: sum(ms[i] for i in range(len(ms)) if names[i % 12] == n) / reps for n in names}
+        per_step = len(ms) // reps          # 12, or 14 with the recomputed QKV and up-projection GEMMs
+        assert len(ms) == per_step * reps and per_step in (12, 14), len(ms)
+        if per_step == 14:                  # launch order: 4 fwd, then recomputed qkv_fwd and up_fwd, then 8 bwd
+            order = names[:4] + ["qkv_fwd", "up_fwd"] + names[4:]
+        else:
+            order = names
+        per = {n: sum(ms[i] for i in range(len(ms)) if order[i % per_step] == n) / reps for n in names}
+        if per_step == 14:
+            for n in ("qkv_fwd", "up_fwd"):
+                flops[n] *= 2
         tot_ms, tot_fl = sum(per.values()), sum(flops.values())
         achieved = tot_fl / (tot_ms * 1e-3) / 1e12
         traffic = None
@@ -186,7 +271,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "pct_of_peak": round(100.0 * tflops / peak, 2), "peak_tflops": peak,
         "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
-        "config": {"workload": f"config {cfg.cfg_id}: {cfg.name}", "hidden": cfg.hidden, "heads": cfg.heads,
+        "config": {"workload": f"config {cfg.cfg_id}: {cfg.name}" + (" (activation-checkpoint backward)" if ckpt else ""), "hidden": cfg.hidden, "heads": cfg.heads,
                    "head_dim": cfg.head_dim, "tp_degree": cfg.tp_degree, "tp_rank": cfg.tp_rank, "seq": cfg.seq,
                    "micro_batch": cfg.micro_batch, "causal": cfg.causal, "row_epilogue": cfg.row_epilogue,
                    "model_tflop_per_step": round((f_fwd + f_bwd) / 1e12, 4),

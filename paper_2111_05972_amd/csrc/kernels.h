@@ -61,11 +61,12 @@ struct LnArgs {
     void* y;
     float* mean; float* rstd;              // [M]
     const void* dy; void* dz; void* dgamma; void* dbeta;   // bwd
-    float* partials;                       // bwd scratch: ln_partial_rows(M) x 2 x H floats
+    float* partials;                       // bwd scratch: ln_scratch_bytes(M, H)
     hipStream_t stream;
 };
 bool ln_supported(int64_t H);
 int64_t ln_partial_rows(int64_t M);
+size_t ln_scratch_bytes(int64_t M, int64_t H);
 hipError_t ln_fwd(const LnArgs& a);
 hipError_t ln_bwd(const LnArgs& a);
 

@@ -5,8 +5,9 @@
 // accesses, up to 8 chunks of 8 elements per thread: H <= 16384), so every tensor is read or written
 // exactly once:
 //   forward : reads a (and b), writes z = a + b (optional) and y          -> up to 4 M H elements
-//   backward: reads dy and z, writes dz; per-workgroup column partials of dgamma, dbeta are then
-//             summed in workgroup order by a second small kernel (fixed order: deterministic).
+//   backward: a row pass reads dy, z for the two per-row means; a tile pass (32 rows x 512 columns per
+//             workgroup) reads dy, z again (served by the infinity cache), writes dz and per-slab column
+//             partials of dgamma, dbeta, which a small kernel sums in slab order (deterministic).
 #include <hip/hip_runtime.h>
 
 #include "device_math.h"
@@ -15,7 +16,6 @@
 namespace tpl {
 
 constexpr int LN_THREADS = 256;
-constexpr int LN_MAX_BLOCKS = 256;     // backward: rows are strided over this many workgroups
 
 // Sum over the workgroup, same value returned to every thread; fixed combination order.
 __device__ __forceinline__ float block_sum(float v, float* red) {
@@ -85,69 +85,100 @@ __global__ __launch_bounds__(LN_THREADS) void ln_fwd_kernel(int64_t M, int64_t H
     }
 }
 
+// Backward, pass 1: per-row means c1 = mean_H(dy*gamma), c2 = mean_H(dy*gamma*zh) (one workgroup per row).
 template <typename T, int MAXC>
-__global__ __launch_bounds__(LN_THREADS) void ln_bwd_kernel(int64_t M, int64_t H, const T* __restrict__ dy,
-                                                            const T* __restrict__ z,
-                                                            const float* __restrict__ mean,
-                                                            const float* __restrict__ rstd,
-                                                            const T* __restrict__ gamma,
-                                                            T* __restrict__ dz,
-                                                            float* __restrict__ partials) {
+__global__ __launch_bounds__(LN_THREADS) void ln_bwd_rowstat_kernel(int64_t M, int64_t H,
+                                                                    const T* __restrict__ dy,
+                                                                    const T* __restrict__ z,
+                                                                    const float* __restrict__ mean,
+                                                                    const float* __restrict__ rstd,
+                                                                    const T* __restrict__ gamma,
+                                                                    float* __restrict__ c12) {
     __shared__ float red[4];
     const int t = threadIdx.x;
     const float inv_h = 1.0f / (float)H;
-    float gam[MAXC][8], dgam[MAXC][8], dbet[MAXC][8];
-#pragma unroll
-    for (int i = 0; i < MAXC; ++i) {
-        const int64_t col = ((int64_t)t + LN_THREADS * i) * 8;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { gam[i][e] = 0.0f; dgam[i][e] = 0.0f; dbet[i][e] = 0.0f; }
-        if (col < H) load8(gamma + col, gam[i]);
-    }
     for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
         const float mu = mean[row], rs = rstd[row];
-        float g[MAXC][8], zh[MAXC][8];
         float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
         for (int i = 0; i < MAXC; ++i) {
             const int64_t col = ((int64_t)t + LN_THREADS * i) * 8;
             if (col < H) {
-                load8(dy + row * H + col, g[i]);
-                load8(z + row * H + col, zh[i]);
+                float g[8], zz[8], gm[8];
+                load8(dy + row * H + col, g);
+                load8(z + row * H + col, zz);
+                load8(gamma + col, gm);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    zh[i][e] = (zh[i][e] - mu) * rs;
-                    dbet[i][e] += g[i][e];
-                    dgam[i][e] = fmaf(g[i][e], zh[i][e], dgam[i][e]);
-                    g[i][e] *= gam[i][e];
-                    s1 += g[i][e];
-                    s2 = fmaf(g[i][e], zh[i][e], s2);
+                    float gg = g[e] * gm[e];
+                    s1 += gg;
+                    s2 = fmaf(gg, (zz[e] - mu) * rs, s2);
                 }
             }
         }
         const float c1 = block_sum(s1, red) * inv_h;
         const float c2 = block_sum(s2, red) * inv_h;
+        if (t == 0) { c12[2 * row] = c1; c12[2 * row + 1] = c2; }
+    }
+}
+
+// Backward, pass 2: a workgroup owns LN_SLAB rows x 512 columns (64 column groups of 8 x 4 row lanes):
+// writes dz for its tile and its column partial sums of dgamma, dbeta (row lanes combined through LDS
+// in lane order).  partials[slab][0][:] = dgamma, partials[slab][1][:] = dbeta.
+constexpr int LN_SLAB = 32;
+template <typename T>
+__global__ __launch_bounds__(LN_THREADS) void ln_bwd_tile_kernel(int64_t M, int64_t H, const T* __restrict__ dy,
+                                                                 const T* __restrict__ z,
+                                                                 const float* __restrict__ mean,
+                                                                 const float* __restrict__ rstd,
+                                                                 const T* __restrict__ gamma,
+                                                                 const float* __restrict__ c12,
+                                                                 T* __restrict__ dz,
+                                                                 float* __restrict__ partials) {
+    __shared__ float red[2][4][64][8];
+    const int cg = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const int64_t col = ((int64_t)blockIdx.x * 64 + cg) * 8;
+    const int64_t m0 = (int64_t)blockIdx.y * LN_SLAB, m1 = m0 + LN_SLAB < M ? m0 + LN_SLAB : M;
+    float dgam[8] = {0, 0, 0, 0, 0, 0, 0, 0}, dbet[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (col < H) {
+        float gm[8];
+        load8(gamma + col, gm);
+        for (int64_t row = m0 + rl; row < m1; row += 4) {
+            const float mu = mean[row], rs = rstd[row], c1 = c12[2 * row], c2 = c12[2 * row + 1];
+            float g[8], zz[8];
+            load8(dy + row * H + col, g);
+            load8(z + row * H + col, zz);
 #pragma unroll
-        for (int i = 0; i < MAXC; ++i) {
-            const int64_t col = ((int64_t)t + LN_THREADS * i) * 8;
-            if (col < H) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) g[i][e] = (g[i][e] - c1 - zh[i][e] * c2) * rs;
-                store8(dz + row * H + col, g[i]);
+            for (int e = 0; e < 8; ++e) {
+                const float zh = (zz[e] - mu) * rs;
+                dbet[e] += g[e];
+                dgam[e] = fmaf(g[e], zh, dgam[e]);
+                g[e] = (g[e] * gm[e] - c1 - zh * c2) * rs;
             }
+            store8(dz + row * H + col, g);
         }
     }
-    // this workgroup's share of the column sums: partials[block][0][:] = dgamma, [block][1][:] = dbeta
-    float* pg = partials + (int64_t)blockIdx.x * 2 * H;
 #pragma unroll
-    for (int i = 0; i < MAXC; ++i) {
-        const int64_t col = ((int64_t)t + LN_THREADS * i) * 8;
-        if (col < H) { store8(pg + col, dgam[i]); store8(pg + H + col, dbet[i]); }
+    for (int e = 0; e < 8; ++e) { red[0][rl][cg][e] = dgam[e]; red[1][rl][cg][e] = dbet[e]; }
+    __syncthreads();
+    if (rl == 0 && col < H) {
+        float* pg = partials + (int64_t)blockIdx.y * 2 * H + col;
+        float a[8], b[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            a[e] = ((red[0][0][cg][e] + red[0][1][cg][e]) + red[0][2][cg][e]) + red[0][3][cg][e];
+            b[e] = ((red[1][0][cg][e] + red[1][1][cg][e]) + red[1][2][cg][e]) + red[1][3][cg][e];
+        }
+        store8(pg, a);
+        store8(pg + H, b);
     }
 }
 
 bool ln_supported(int64_t H) { return H > 0 && H % 8 == 0 && H <= 8 * 8 * LN_THREADS; }
-int64_t ln_partial_rows(int64_t M) { return M < LN_MAX_BLOCKS ? M : LN_MAX_BLOCKS; }
+int64_t ln_partial_rows(int64_t M) { return (M + LN_SLAB - 1) / LN_SLAB; }
+size_t ln_scratch_bytes(int64_t M, int64_t H) {
+    return ((size_t)2 * M + (size_t)ln_partial_rows(M) * 2 * H) * sizeof(float);
+}
 
 template <typename T, int MAXC>
 static hipError_t fwd_t(const LnArgs& a) {
@@ -159,17 +190,21 @@ static hipError_t fwd_t(const LnArgs& a) {
 }
 template <typename T, int MAXC>
 static hipError_t bwd_t(const LnArgs& a) {
-    const int64_t blocks = ln_partial_rows(a.M);
-    hipLaunchKernelGGL((ln_bwd_kernel<T, MAXC>), dim3((unsigned)blocks), dim3(LN_THREADS), 0, a.stream, a.M,
-                       a.H, (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma, (T*)a.dz,
-                       a.partials);
+    float* c12 = a.partials;                       // [M][2], then the column partials
+    float* part = a.partials + 2 * a.M;
+    const unsigned grid = (unsigned)(a.M < 65535 * 16 ? a.M : 65535 * 16);
+    hipLaunchKernelGGL((ln_bwd_rowstat_kernel<T, MAXC>), dim3(grid), dim3(LN_THREADS), 0, a.stream, a.M, a.H,
+                       (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma, c12);
+    const int64_t slabs = ln_partial_rows(a.M);
+    hipLaunchKernelGGL((ln_bwd_tile_kernel<T>), dim3((unsigned)((a.H + 511) / 512), (unsigned)slabs),
+                       dim3(LN_THREADS), 0, a.stream, a.M, a.H, (const T*)a.dy, (const T*)a.z, a.mean, a.rstd,
+                       (const T*)a.gamma, c12, (T*)a.dz, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // partial rows are [block][2][H]: summing over blocks with row length 2H yields dgamma | dbeta
-    // into a [2H] vector; gamma and beta gradients are separate buffers, so two calls with stride 2H.
-    e = sum_partials_strided(a.dtype, blocks, a.H, a.partials, 2 * a.H, a.dgamma, a.stream);
+    // partial rows are [slab][2][H]: gamma and beta gradients are separate buffers, so two strided sums
+    e = sum_partials_strided(a.dtype, slabs, a.H, part, 2 * a.H, a.dgamma, a.stream);
     if (e != hipSuccess) return e;
-    return sum_partials_strided(a.dtype, blocks, a.H, a.partials + a.H, 2 * a.H, a.dbeta, a.stream);
+    return sum_partials_strided(a.dtype, slabs, a.H, part + a.H, 2 * a.H, a.dbeta, a.stream);
 }
 
 template <typename T>

@@ -334,7 +334,7 @@ static int ln_check(int dtype, int64_t M, int64_t H) {
 
 size_t tp_layer_ln_workspace_bytes(int64_t M, int64_t H) {
     if (M <= 0 || H <= 0) return 0;
-    return up((size_t)ln_partial_rows(M) * 2 * (size_t)H * sizeof(float));
+    return up(ln_scratch_bytes(M, H));
 }
 
 int tp_layer_ln_fwd(int dtype, int64_t M, int64_t H, const void* a, const void* b, const void* gamma,
