@@ -71,20 +71,26 @@ struct GemmParams {
 // ---- LDS layouts -------------------------------------------------------------------------------
 // K-major stage tile: 64-byte rows (32 k), four 16-byte chunks, swizzled by row.
 __device__ __forceinline__ int swz_k32(int row) { return (row >> 2) & 3; }
-// MN-major stage tile: one row of R (m or n) bf16 per k = R/8 16-byte chunks.  A transposing read
-// touches four consecutive k at the same columns, so consecutive k are displaced by 64 bytes:
-// XOR of chunk bits 2-3 when the chunk count is a power of two, a rotation otherwise.
+// MN-major stage tile: one row of R (m or n) bf16 per k = R/8 16-byte chunks, R*2 bytes per k.
+// A transposing read touches four consecutive k at the same 64 bytes of columns (two 16-lane groups,
+// 32 bytes each); the four k must land in four different 64-byte quarters of the 256-byte bank line.
+//  * R*2 a multiple of 256 (R = 128, 256): every k starts at the same bank offset, so the 64-byte
+//    column group is XORed with k & 3.
+//  * R = 192 (384-byte rows): k and k+1 already differ by 128 bytes, so k+2, k+3 are moved one
+//    64-byte group further (cyclically over the row's 6 groups; 6 = 2 mod 4 keeps the four distinct).
 template <int R> __device__ __forceinline__ int mn_swz(int c, int k) {
     constexpr int CPR = R / 8;
     if ((CPR & (CPR - 1)) == 0) return c ^ ((k & 3) << 2);
-    int x = c + ((k & 3) << 2);
-    return x >= CPR ? x - CPR : x;
+    int g = (c >> 2) + ((k >> 1) & 1);
+    g = g >= CPR / 4 ? g - CPR / 4 : g;
+    return (g << 2) | (c & 3);
 }
 template <int R> __device__ __forceinline__ int mn_unswz(int c, int k) {
     constexpr int CPR = R / 8;
     if ((CPR & (CPR - 1)) == 0) return c ^ ((k & 3) << 2);
-    int x = c - ((k & 3) << 2);
-    return x < 0 ? x + CPR : x;
+    int g = (c >> 2) - ((k >> 1) & 1);
+    g = g < 0 ? g + CPR / 4 : g;
+    return (g << 2) | (c & 3);
 }
 
 // Raw buffer descriptor over `bytes` bytes at p (stride 0): loads at offsets >= bytes return zero
