@@ -47,28 +47,29 @@ template <int DH> __device__ __forceinline__ int swz(int row) {
                     : (((row & 3) << 2) | ((row >> 2) & 3));           // 256-byte rows, 16 chunks
 }
 template <int DH> constexpr int tile_bytes() { return TILE * DH * 2; }
-template <int DH> constexpr int chunks_per_thread() { return TILE * DH / 8 / ATHREADS; }
+template <int DH, int NT> constexpr int NCHUNKS = TILE * DH / 8 / NT;     // 16-byte chunks per thread and tile
+template <int DH> constexpr int chunks_per_thread() { return NCHUNKS<DH, ATHREADS>; }
 
 // global -> registers; rows >= nrows read as zero.  base points at row 0, column 0 of the head.
-template <int DH>
-__device__ __forceinline__ void tile_g2r(uint4 (&r)[chunks_per_thread<DH>()], const bf16_t* base,
+template <int DH, int NT = ATHREADS>
+__device__ __forceinline__ void tile_g2r(uint4 (&r)[(NCHUNKS<DH, NT>)], const bf16_t* base,
                                          int64_t ld, int row0, int nrows, int t) {
     constexpr int NC = DH / 8;
 #pragma unroll
-    for (int i = 0; i < chunks_per_thread<DH>(); ++i) {
-        int q = t + ATHREADS * i;
+    for (int i = 0; i < NCHUNKS<DH, NT>; ++i) {
+        int q = t + NT * i;
         int row = q / NC, c = q % NC;
         uint4 v = make_uint4(0, 0, 0, 0);
         if (row0 + row < nrows) v = *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + row) * ld + c * 8);
         r[i] = v;
     }
 }
-template <int DH>
-__device__ __forceinline__ void tile_r2s(char* tile, const uint4 (&r)[chunks_per_thread<DH>()], int t) {
+template <int DH, int NT = ATHREADS>
+__device__ __forceinline__ void tile_r2s(char* tile, const uint4 (&r)[(NCHUNKS<DH, NT>)], int t) {
     constexpr int NC = DH / 8;
 #pragma unroll
-    for (int i = 0; i < chunks_per_thread<DH>(); ++i) {
-        int q = t + ATHREADS * i;
+    for (int i = 0; i < NCHUNKS<DH, NT>; ++i) {
+        int q = t + NT * i;
         int row = q / NC, c = q % NC;
         *reinterpret_cast<uint4*>(tile + row * (DH * 2) + ((c ^ swz<DH>(row)) << 4)) = r[i];
     }
@@ -129,17 +130,29 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
 // =================================================================================================
-// Forward.  Workgroup = (query block of 128, batch*head); wavefront = 32 queries; K/V streamed in
-// tiles of 64 keys through double-buffered LDS.
+// Forward.  Workgroup = (query block of 128, batch*head), 8 wavefronts: wavefront w owns the 32
+// queries of sub-block w % 4 and, of every 64-key tile streamed through double-buffered LDS, the key
+// half w / 4.  The two wavefronts of a query sub-block therefore walk half the keys each (half the
+// dependent chain, two wavefronts per SIMD to overlap softmax arithmetic with matrix-core work) and
+// their (max, sum, O) partials are merged through LDS at the end, always in the same order.
 // =================================================================================================
+constexpr int FTHREADS = 512;
+
+template <int DH> constexpr int fwd_lds_bytes() {
+    constexpr int ring = 4 * tile_bytes<DH>();
+    constexpr int merge = 4 * 64 * (2 + DH / 2) * 4;      // per query sub-block and lane: m, l, O[DH/2]
+    return ring > merge ? ring : merge;
+}
+
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(ATHREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(FTHREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
                                                             bf16_t* __restrict__ o,
                                                             float* __restrict__ lse, int S, int nl) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TB = tile_bytes<DH>();
-    constexpr int NCH = chunks_per_thread<DH>();
+    constexpr int NCH = NCHUNKS<DH, FTHREADS>;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5;
+    const int qs = wave & 3, kvh = wave >> 2;
     const int nqb = (S + BLK - 1) / BLK;
     const int qb = nqb - 1 - (int)blockIdx.x;            // longest (last) causal blocks first
     const int b = blockIdx.y / nl, h = blockIdx.y % nl;
@@ -147,7 +160,7 @@ __global__ __launch_bounds__(ATHREADS) void attn_fwd_kernel(const bf16_t* __rest
     const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * DH;
     const bf16_t* kbase = qbase + (int64_t)nl * DH;
     const bf16_t* vbase = kbase + (int64_t)nl * DH;
-    const int q0 = qb * BLK + wave * 32;                  // first query of this wavefront
+    const int q0 = qb * BLK + qs * 32;                    // first query of this wavefront
     const int q = q0 + (lane & 31);                       // this lane's query
     const float c2 = LOG2E / sqrtf((float)DH);
 
@@ -163,10 +176,10 @@ __global__ __launch_bounds__(ATHREADS) void attn_fwd_kernel(const bf16_t* __rest
     const int kv_end = CAUSAL ? min(S, (qb + 1) * BLK) : S;
     const int ntiles = (kv_end + TILE - 1) / TILE;
     uint4 rk[NCH], rv[NCH];
-    tile_g2r<DH>(rk, kbase, ld, 0, S, t);
-    tile_g2r<DH>(rv, vbase, ld, 0, S, t);
-    tile_r2s<DH>(smem, rk, t);
-    tile_r2s<DH>(smem + TB, rv, t);
+    tile_g2r<DH, FTHREADS>(rk, kbase, ld, 0, S, t);
+    tile_g2r<DH, FTHREADS>(rv, vbase, ld, 0, S, t);
+    tile_r2s<DH, FTHREADS>(smem, rk, t);
+    tile_r2s<DH, FTHREADS>(smem + TB, rv, t);
     __syncthreads();
     for (int kt = 0; kt < ntiles; ++kt) {
         const char* ks_ = smem + (kt & 1) * 2 * TB;
@@ -174,16 +187,14 @@ __global__ __launch_bounds__(ATHREADS) void attn_fwd_kernel(const bf16_t* __rest
         char* nxt = smem + ((kt + 1) & 1) * 2 * TB;
         const bool more = kt + 1 < ntiles;
         if (more) {
-            tile_g2r<DH>(rk, kbase, ld, (kt + 1) * TILE, S, t);
-            tile_g2r<DH>(rv, vbase, ld, (kt + 1) * TILE, S, t);
+            tile_g2r<DH, FTHREADS>(rk, kbase, ld, (kt + 1) * TILE, S, t);
+            tile_g2r<DH, FTHREADS>(rv, vbase, ld, (kt + 1) * TILE, S, t);
         }
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb) {
-            const int kv0 = kt * TILE + sb * 32;
-            if (kv0 >= kv_end || (CAUSAL && kv0 > q0 + 31)) continue;     // wavefront-uniform
+        const int kv0 = kt * TILE + kvh * 32;
+        if (kv0 < kv_end && !(CAUSAL && kv0 > q0 + 31)) {                 // wavefront-uniform
             f32x16 s = zero16();
 #pragma unroll
-            for (int ks = 0; ks < DH / 16; ++ks) s = MFMA(frag_k<DH>(ks_, sb * 32, ks, lane), qf[ks], s);
+            for (int ks = 0; ks < DH / 16; ++ks) s = MFMA(frag_k<DH>(ks_, kvh * 32, ks, lane), qf[ks], s);
             // masking is needed only in tiles that straddle the diagonal or the end of the sequence
             if (kv0 + 31 >= S || (CAUSAL && kv0 + 31 > q0)) {
 #pragma unroll
@@ -214,27 +225,49 @@ __global__ __launch_bounds__(ATHREADS) void attn_fwd_kernel(const bf16_t* __rest
             bf16x8 pb0 = pack_regs(s, 0), pb1 = pack_regs(s, 8);
 #pragma unroll
             for (int dt = 0; dt < DH / 32; ++dt) {
-                oacc[dt] = MFMA(frag_t<DH>(vs_, dt * 32, sb * 32, lane), pb0, oacc[dt]);
-                oacc[dt] = MFMA(frag_t<DH>(vs_, dt * 32, sb * 32 + 16, lane), pb1, oacc[dt]);
+                oacc[dt] = MFMA(frag_t<DH>(vs_, dt * 32, kvh * 32, lane), pb0, oacc[dt]);
+                oacc[dt] = MFMA(frag_t<DH>(vs_, dt * 32, kvh * 32 + 16, lane), pb1, oacc[dt]);
             }
         }
         if (more) {
-            tile_r2s<DH>(nxt, rk, t);
-            tile_r2s<DH>(nxt + TB, rv, t);
+            tile_r2s<DH, FTHREADS>(nxt, rk, t);
+            tile_r2s<DH, FTHREADS>(nxt + TB, rv, t);
         }
         __syncthreads();
     }
     lsum += __shfl_xor(lsum, 32, 64);
-    const float inv = lsum > 0.0f ? 1.0f / lsum : 0.0f;
-    if (q < S) {
-        bf16_t* op = o + ((int64_t)b * S + q) * ((int64_t)nl * DH) + (int64_t)h * DH;
+    // merge the two key halves: wavefronts 4..7 hand (m, l, O) to wavefronts 0..3 through LDS
+    constexpr int NV = 2 + DH / 2;
+    float* mg = reinterpret_cast<float*>(smem) + (qs * NV) * 64 + lane;   // element i at mg[i * 64]
+    if (kvh == 1) {
+        mg[0] = m; mg[64] = lsum;
 #pragma unroll
         for (int dt = 0; dt < DH / 32; ++dt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                store4(op + dt * 32 + 8 * i + 4 * half, oacc[dt][4 * i] * inv, oacc[dt][4 * i + 1] * inv,
-                       oacc[dt][4 * i + 2] * inv, oacc[dt][4 * i + 3] * inv);
-        if (half == 0) lse[((int64_t)b * nl + h) * S + q] = (m + log2f(lsum)) * LN2;
+            for (int v = 0; v < 16; ++v) mg[(2 + dt * 16 + v) * 64] = oacc[dt][v];
+    }
+    __syncthreads();
+    if (kvh == 0) {
+        const float m1 = mg[0], l1 = mg[64];
+        const float mn = fmaxf(m, m1);
+        const float mu = mn == -INFINITY ? 0.0f : mn;
+        const float f0 = fast_exp2(m - mu), f1 = fast_exp2(m1 - mu);
+        const float ltot = lsum * f0 + l1 * f1;
+        const float inv = ltot > 0.0f ? 1.0f / ltot : 0.0f;
+        if (q < S) {
+            bf16_t* op = o + ((int64_t)b * S + q) * ((int64_t)nl * DH) + (int64_t)h * DH;
+#pragma unroll
+            for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float r[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        r[j] = (oacc[dt][4 * i + j] * f0 + mg[(2 + dt * 16 + 4 * i + j) * 64] * f1) * inv;
+                    store4(op + dt * 32 + 8 * i + 4 * half, r[0], r[1], r[2], r[3]);
+                }
+            if (half == 0) lse[((int64_t)b * nl + h) * S + q] = (mn + log2f(ltot)) * LN2;
+        }
     }
 }
 
@@ -267,19 +300,20 @@ __global__ __launch_bounds__(256) void attn_dsum_kernel(const bf16_t* __restrict
 }
 
 // =================================================================================================
-// dK, dV.  Workgroup = (key block of 128, batch*head); wavefront = 32 keys whose K and V fragments
-// stay in registers; Q, dO (and LSE, D) are streamed in tiles of 64 queries.
-// Score tile is untransposed: lane = key (l%32), registers = queries 8i + 4*(l/32) + j.
+// dK, dV.  Workgroup = (key block of 128, batch*head), 8 wavefronts: wavefront w owns the 32 keys of
+// sub-block w % 4; wavefronts 0..3 accumulate dV = P^T dO (they need the scores only), wavefronts 4..7
+// accumulate dK = dS^T Q (scores and dP).  The scores are computed by both, which costs a quarter more
+// matrix-core work but halves the accumulators and fragments a wavefront holds (two wavefronts per
+// SIMD) and shortens its dependent chain per tile.  Q, dO (and LSE, D) are streamed in tiles of 64
+// queries.  Score tile is untransposed: lane = key (l%32), registers = queries 8i + 4*(l/32) + j.
 // =================================================================================================
-template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(ATHREADS) void attn_dkv_kernel(const bf16_t* __restrict__ qkv,
-                                                            const bf16_t* __restrict__ d_o,
-                                                            const float* __restrict__ lse,
-                                                            const float* __restrict__ dsum,
-                                                            bf16_t* __restrict__ dqkv, int S, int nl) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+template <int DH, bool CAUSAL, bool DK_ROLE>
+__device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restrict__ qkv,
+                                              const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
+                                              const float* __restrict__ dsum, bf16_t* __restrict__ dqkv,
+                                              int S, int nl) {
     constexpr int TB = tile_bytes<DH>();
-    constexpr int NCH = chunks_per_thread<DH>();
+    constexpr int NCH = NCHUNKS<DH, FTHREADS>;
     constexpr int STAGE = 2 * TB + 2 * TILE * 4;          // Q tile, dO tile, LSE*log2e, D
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5;
     const int kb = blockIdx.x;
@@ -291,28 +325,28 @@ __global__ __launch_bounds__(ATHREADS) void attn_dkv_kernel(const bf16_t* __rest
     const bf16_t* dobase = d_o + (int64_t)b * S * ldo + (int64_t)h * DH;
     const float* lrow = lse + ((int64_t)b * nl + h) * S;
     const float* drow = dsum + ((int64_t)b * nl + h) * S;
-    const int k0 = kb * BLK + wave * 32;
+    const int k0 = kb * BLK + (wave & 3) * 32;
     const int kv = k0 + (lane & 31);
     const float scale = 1.0f / sqrtf((float)DH);
     const float c2 = LOG2E * scale;
 
-    bf16x8 kf[DH / 16], vf[DH / 16];
+    bf16x8 kf[DH / 16], vf[DK_ROLE ? DH / 16 : 1];
 #pragma unroll
     for (int ks = 0; ks < DH / 16; ++ks) {
         kf[ks] = frag_k_global<DH>(kbase, ld, kv, S, ks, lane);
-        vf[ks] = frag_k_global<DH>(vbase, ld, kv, S, ks, lane);
+        if (DK_ROLE) vf[ks] = frag_k_global<DH>(vbase, ld, kv, S, ks, lane);
     }
-    f32x16 dk[DH / 32], dv[DH / 32];
+    f32x16 acc[DH / 32];                                   // dK (DK_ROLE) or dV
 #pragma unroll
-    for (int dt = 0; dt < DH / 32; ++dt) { dk[dt] = zero16(); dv[dt] = zero16(); }
+    for (int dt = 0; dt < DH / 32; ++dt) acc[dt] = zero16();
 
     const int qt0 = CAUSAL ? (kb * BLK) / TILE : 0;       // first query tile that can see this key block
     const int ntiles = (S + TILE - 1) / TILE;
     uint4 rq[NCH], rdo[NCH];
     float rl = 0.0f, rd = 0.0f;
     auto g2r = [&](int qt) {
-        tile_g2r<DH>(rq, qbase, ld, qt * TILE, S, t);
-        tile_g2r<DH>(rdo, dobase, ldo, qt * TILE, S, t);
+        tile_g2r<DH, FTHREADS>(rq, qbase, ld, qt * TILE, S, t);
+        tile_g2r<DH, FTHREADS>(rdo, dobase, ldo, qt * TILE, S, t);
         if (t < TILE) {
             int qi = qt * TILE + t;
             rl = qi < S ? lrow[qi] * LOG2E : 0.0f;
@@ -320,8 +354,8 @@ __global__ __launch_bounds__(ATHREADS) void attn_dkv_kernel(const bf16_t* __rest
         }
     };
     auto r2s = [&](char* st) {
-        tile_r2s<DH>(st, rq, t);
-        tile_r2s<DH>(st + TB, rdo, t);
+        tile_r2s<DH, FTHREADS>(st, rq, t);
+        tile_r2s<DH, FTHREADS>(st + TB, rdo, t);
         if (t < TILE) {
             reinterpret_cast<float*>(st + 2 * TB)[t] = rl;
             reinterpret_cast<float*>(st + 2 * TB)[TILE + t] = rd;
@@ -346,13 +380,14 @@ __global__ __launch_bounds__(ATHREADS) void attn_dkv_kernel(const bf16_t* __rest
 #pragma unroll
             for (int ks = 0; ks < DH / 16; ++ks) {
                 s = MFMA(frag_k<DH>(qs, sb * 32, ks, lane), kf[ks], s);
-                dp = MFMA(frag_k<DH>(dos, sb * 32, ks, lane), vf[ks], dp);
+                if (DK_ROLE) dp = MFMA(frag_k<DH>(dos, sb * 32, ks, lane), vf[ks], dp);
             }
             const bool need_mask = qs0 + 31 >= S || k0 + 31 >= S || (CAUSAL && k0 + 31 > qs0);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float4 l4 = *reinterpret_cast<const float4*>(ls + sb * 32 + 8 * i + 4 * half);
-                const float4 d4 = *reinterpret_cast<const float4*>(ds_ + sb * 32 + 8 * i + 4 * half);
+                float4 d4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (DK_ROLE) d4 = *reinterpret_cast<const float4*>(ds_ + sb * 32 + 8 * i + 4 * half);
                 const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dvv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -363,52 +398,66 @@ __global__ __launch_bounds__(ATHREADS) void attn_dkv_kernel(const bf16_t* __rest
                         bool ok = qi < S && kv < S && (!CAUSAL || kv <= qi);
                         p = ok ? p : 0.0f;
                     }
-                    s[v] = p;
-                    dp[v] = p * (dp[v] - dvv[j]);
+                    s[v] = DK_ROLE ? p * (dp[v] - dvv[j]) : p;             // dS, or P
                 }
             }
-            bf16x8 p0 = pack_regs(s, 0), p1 = pack_regs(s, 8);
-            bf16x8 g0 = pack_regs(dp, 0), g1 = pack_regs(dp, 8);
+            bf16x8 g0 = pack_regs(s, 0), g1 = pack_regs(s, 8);
+            const char* src = DK_ROLE ? qs : dos;                          // dK += dS^T Q ; dV += P^T dO
 #pragma unroll
             for (int dt = 0; dt < DH / 32; ++dt) {
-                dv[dt] = MFMA(frag_t<DH>(dos, dt * 32, sb * 32, lane), p0, dv[dt]);
-                dv[dt] = MFMA(frag_t<DH>(dos, dt * 32, sb * 32 + 16, lane), p1, dv[dt]);
-                dk[dt] = MFMA(frag_t<DH>(qs, dt * 32, sb * 32, lane), g0, dk[dt]);
-                dk[dt] = MFMA(frag_t<DH>(qs, dt * 32, sb * 32 + 16, lane), g1, dk[dt]);
+                acc[dt] = MFMA(frag_t<DH>(src, dt * 32, sb * 32, lane), g0, acc[dt]);
+                acc[dt] = MFMA(frag_t<DH>(src, dt * 32, sb * 32 + 16, lane), g1, acc[dt]);
             }
         }
         if (more) r2s(nxt);
         __syncthreads();
     }
     if (kv < S) {
-        bf16_t* dkp = dqkv + ((int64_t)b * S + kv) * ld + (int64_t)nl * DH + (int64_t)h * DH;
-        bf16_t* dvp = dkp + (int64_t)nl * DH;
+        bf16_t* outp = dqkv + ((int64_t)b * S + kv) * ld + (int64_t)(DK_ROLE ? 1 : 2) * nl * DH + (int64_t)h * DH;
+        const float f = DK_ROLE ? scale : 1.0f;
 #pragma unroll
         for (int dt = 0; dt < DH / 32; ++dt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                int d = dt * 32 + 8 * i + 4 * half;
-                store4(dkp + d, dk[dt][4 * i] * scale, dk[dt][4 * i + 1] * scale, dk[dt][4 * i + 2] * scale,
-                       dk[dt][4 * i + 3] * scale);
-                store4(dvp + d, dv[dt][4 * i], dv[dt][4 * i + 1], dv[dt][4 * i + 2], dv[dt][4 * i + 3]);
-            }
+            for (int i = 0; i < 4; ++i)
+                store4(outp + dt * 32 + 8 * i + 4 * half, acc[dt][4 * i] * f, acc[dt][4 * i + 1] * f,
+                       acc[dt][4 * i + 2] * f, acc[dt][4 * i + 3] * f);
     }
 }
 
-// =================================================================================================
-// dQ.  Workgroup = (query block of 128, batch*head); wavefront = 32 queries whose Q and dO fragments
-// stay in registers; K and V are streamed in tiles of 64 keys.  Transposed score tile: lane = query.
-// =================================================================================================
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(ATHREADS) void attn_dq_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(FTHREADS) void attn_dkv_kernel(const bf16_t* __restrict__ qkv,
+                                                            const bf16_t* __restrict__ d_o,
+                                                            const float* __restrict__ lse,
+                                                            const float* __restrict__ dsum,
+                                                            bf16_t* __restrict__ dqkv, int S, int nl) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    // the role is uniform per wavefront; both bodies run the same loop and the same barriers
+    if ((threadIdx.x >> 6) < 4) attn_dkv_body<DH, CAUSAL, false>(smem, qkv, d_o, lse, dsum, dqkv, S, nl);
+    else attn_dkv_body<DH, CAUSAL, true>(smem, qkv, d_o, lse, dsum, dqkv, S, nl);
+}
+
+// =================================================================================================
+// dQ.  Same decomposition as the forward: 8 wavefronts, wavefront w owns query sub-block w % 4 (its Q
+// and dO fragments stay in registers) and key half w / 4 of every streamed 64-key tile; the two dQ
+// partials of a sub-block are added through LDS in a fixed order.  Transposed score tile: lane = query.
+// =================================================================================================
+template <int DH> constexpr int dq_lds_bytes() {
+    constexpr int ring = 4 * tile_bytes<DH>();
+    constexpr int merge = 4 * 64 * (DH / 2) * 4;
+    return ring > merge ? ring : merge;
+}
+
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(FTHREADS) void attn_dq_kernel(const bf16_t* __restrict__ qkv,
                                                            const bf16_t* __restrict__ d_o,
                                                            const float* __restrict__ lse,
                                                            const float* __restrict__ dsum,
                                                            bf16_t* __restrict__ dqkv, int S, int nl) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TB = tile_bytes<DH>();
-    constexpr int NCH = chunks_per_thread<DH>();
+    constexpr int NCH = NCHUNKS<DH, FTHREADS>;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5;
+    const int qs = wave & 3, kvh = wave >> 2;
     const int nqb = (S + BLK - 1) / BLK;
     const int qb = nqb - 1 - (int)blockIdx.x;
     const int b = blockIdx.y / nl, h = blockIdx.y % nl;
@@ -417,7 +466,7 @@ __global__ __launch_bounds__(ATHREADS) void attn_dq_kernel(const bf16_t* __restr
     const bf16_t* kbase = qbase + (int64_t)nl * DH;
     const bf16_t* vbase = kbase + (int64_t)nl * DH;
     const bf16_t* dobase = d_o + (int64_t)b * S * ldo + (int64_t)h * DH;
-    const int q0 = qb * BLK + wave * 32;
+    const int q0 = qb * BLK + qs * 32;
     const int q = q0 + (lane & 31);
     const float scale = 1.0f / sqrtf((float)DH);
     const float c2 = LOG2E * scale;
@@ -437,10 +486,10 @@ __global__ __launch_bounds__(ATHREADS) void attn_dq_kernel(const bf16_t* __restr
     const int kv_end = CAUSAL ? min(S, (qb + 1) * BLK) : S;
     const int ntiles = (kv_end + TILE - 1) / TILE;
     uint4 rk[NCH], rv[NCH];
-    tile_g2r<DH>(rk, kbase, ld, 0, S, t);
-    tile_g2r<DH>(rv, vbase, ld, 0, S, t);
-    tile_r2s<DH>(smem, rk, t);
-    tile_r2s<DH>(smem + TB, rv, t);
+    tile_g2r<DH, FTHREADS>(rk, kbase, ld, 0, S, t);
+    tile_g2r<DH, FTHREADS>(rv, vbase, ld, 0, S, t);
+    tile_r2s<DH, FTHREADS>(smem, rk, t);
+    tile_r2s<DH, FTHREADS>(smem + TB, rv, t);
     __syncthreads();
     for (int kt = 0; kt < ntiles; ++kt) {
         const char* ks_ = smem + (kt & 1) * 2 * TB;
@@ -448,18 +497,16 @@ __global__ __launch_bounds__(ATHREADS) void attn_dq_kernel(const bf16_t* __restr
         char* nxt = smem + ((kt + 1) & 1) * 2 * TB;
         const bool more = kt + 1 < ntiles;
         if (more) {
-            tile_g2r<DH>(rk, kbase, ld, (kt + 1) * TILE, S, t);
-            tile_g2r<DH>(rv, vbase, ld, (kt + 1) * TILE, S, t);
+            tile_g2r<DH, FTHREADS>(rk, kbase, ld, (kt + 1) * TILE, S, t);
+            tile_g2r<DH, FTHREADS>(rv, vbase, ld, (kt + 1) * TILE, S, t);
         }
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb) {
-            const int kv0 = kt * TILE + sb * 32;
-            if (kv0 >= kv_end || (CAUSAL && kv0 > q0 + 31)) continue;
+        const int kv0 = kt * TILE + kvh * 32;
+        if (kv0 < kv_end && !(CAUSAL && kv0 > q0 + 31)) {                 // wavefront-uniform
             f32x16 s = zero16(), dp = zero16();
 #pragma unroll
             for (int ks = 0; ks < DH / 16; ++ks) {
-                s = MFMA(frag_k<DH>(ks_, sb * 32, ks, lane), qf[ks], s);
-                dp = MFMA(frag_k<DH>(vs_, sb * 32, ks, lane), dof[ks], dp);
+                s = MFMA(frag_k<DH>(ks_, kvh * 32, ks, lane), qf[ks], s);
+                dp = MFMA(frag_k<DH>(vs_, kvh * 32, ks, lane), dof[ks], dp);
             }
             const bool need_mask = q0 + 31 >= S || kv0 + 31 >= S || (CAUSAL && kv0 + 31 > q0);
 #pragma unroll
@@ -475,24 +522,35 @@ __global__ __launch_bounds__(ATHREADS) void attn_dq_kernel(const bf16_t* __restr
             bf16x8 g0 = pack_regs(dp, 0), g1 = pack_regs(dp, 8);
 #pragma unroll
             for (int dt = 0; dt < DH / 32; ++dt) {
-                dq[dt] = MFMA(frag_t<DH>(ks_, dt * 32, sb * 32, lane), g0, dq[dt]);
-                dq[dt] = MFMA(frag_t<DH>(ks_, dt * 32, sb * 32 + 16, lane), g1, dq[dt]);
+                dq[dt] = MFMA(frag_t<DH>(ks_, dt * 32, kvh * 32, lane), g0, dq[dt]);
+                dq[dt] = MFMA(frag_t<DH>(ks_, dt * 32, kvh * 32 + 16, lane), g1, dq[dt]);
             }
         }
         if (more) {
-            tile_r2s<DH>(nxt, rk, t);
-            tile_r2s<DH>(nxt + TB, rv, t);
+            tile_r2s<DH, FTHREADS>(nxt, rk, t);
+            tile_r2s<DH, FTHREADS>(nxt + TB, rv, t);
         }
         __syncthreads();
     }
-    if (q < S) {
+    float* mg = reinterpret_cast<float*>(smem) + (qs * (DH / 2)) * 64 + lane;   // element i at mg[i * 64]
+    if (kvh == 1) {
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mg[(dt * 16 + v) * 64] = dq[dt][v];
+    }
+    __syncthreads();
+    if (kvh == 0 && q < S) {
         bf16_t* dqp = dqkv + ((int64_t)b * S + q) * ld + (int64_t)h * DH;
 #pragma unroll
         for (int dt = 0; dt < DH / 32; ++dt)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                store4(dqp + dt * 32 + 8 * i + 4 * half, dq[dt][4 * i] * scale, dq[dt][4 * i + 1] * scale,
-                       dq[dt][4 * i + 2] * scale, dq[dt][4 * i + 3] * scale);
+            for (int i = 0; i < 4; ++i) {
+                float r[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) r[j] = (dq[dt][4 * i + j] + mg[(dt * 16 + 4 * i + j) * 64]) * scale;
+                store4(dqp + dt * 32 + 8 * i + 4 * half, r[0], r[1], r[2], r[3]);
+            }
     }
 }
 
@@ -509,7 +567,7 @@ static hipError_t set_lds(K kernel, int bytes) {
 
 template <int DH, bool CAUSAL>
 static hipError_t fwd_t(const AttnArgs& a) {
-    constexpr int LDS = 4 * tile_bytes<DH>();
+    constexpr int LDS = fwd_lds_bytes<DH>();
     static bool once = false;
     if (!once) {
         hipError_t e = set_lds(&attn_fwd_kernel<DH, CAUSAL>, LDS);
@@ -517,7 +575,7 @@ static hipError_t fwd_t(const AttnArgs& a) {
         once = true;
     }
     dim3 grid((a.S + BLK - 1) / BLK, a.B * a.nl);
-    hipLaunchKernelGGL((attn_fwd_kernel<DH, CAUSAL>), grid, dim3(ATHREADS), LDS, a.stream,
+    hipLaunchKernelGGL((attn_fwd_kernel<DH, CAUSAL>), grid, dim3(FTHREADS), LDS, a.stream,
                        (const bf16_t*)a.qkv, (bf16_t*)a.o, a.lse, a.S, a.nl);
     return hipGetLastError();
 }
@@ -525,7 +583,7 @@ static hipError_t fwd_t(const AttnArgs& a) {
 template <int DH, bool CAUSAL>
 static hipError_t bwd_t(const AttnArgs& a) {
     constexpr int LDS_KV = 2 * (2 * tile_bytes<DH>() + 2 * TILE * 4);
-    constexpr int LDS_Q = 4 * tile_bytes<DH>();
+    constexpr int LDS_Q = dq_lds_bytes<DH>();
     static bool once = false;
     if (!once) {
         hipError_t e = set_lds(&attn_dkv_kernel<DH, CAUSAL>, LDS_KV);
@@ -538,9 +596,9 @@ static hipError_t bwd_t(const AttnArgs& a) {
     hipLaunchKernelGGL((attn_dsum_kernel<DH>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, a.stream,
                        (const bf16_t*)a.o, (const bf16_t*)a.d_o, a.dsum, a.B, a.S, a.nl);
     dim3 grid((a.S + BLK - 1) / BLK, a.B * a.nl);
-    hipLaunchKernelGGL((attn_dkv_kernel<DH, CAUSAL>), grid, dim3(ATHREADS), LDS_KV, a.stream,
+    hipLaunchKernelGGL((attn_dkv_kernel<DH, CAUSAL>), grid, dim3(FTHREADS), LDS_KV, a.stream,
                        (const bf16_t*)a.qkv, (const bf16_t*)a.d_o, a.lse, a.dsum, (bf16_t*)a.dqkv, a.S, a.nl);
-    hipLaunchKernelGGL((attn_dq_kernel<DH, CAUSAL>), grid, dim3(ATHREADS), LDS_Q, a.stream,
+    hipLaunchKernelGGL((attn_dq_kernel<DH, CAUSAL>), grid, dim3(FTHREADS), LDS_Q, a.stream,
                        (const bf16_t*)a.qkv, (const bf16_t*)a.d_o, a.lse, a.dsum, (bf16_t*)a.dqkv, a.S, a.nl);
     return hipGetLastError();
 }
