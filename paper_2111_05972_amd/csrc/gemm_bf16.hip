@@ -6,9 +6,17 @@
 // fills the last round over the compute units badly or whose K is short; the host picks by estimate.
 // K is walked in stages of 32 through a 4-deep LDS ring (4 x 32 KiB) that is filled by
 // buffer_load ... lds: global memory goes straight into LDS, no staging registers, and anything
-// outside the matrix is zero filled by the buffer bounds check.  Loads run about 3.5 stages ahead of
-// the math.  There is one barrier per stage, placed between the two 16-MFMA halves of the stage so
-// that its wait and the LDS reads that follow it overlap with matrix-core work already queued.
+// outside the matrix is zero filled by the buffer bounds check.  Loads run about 3 stages ahead of
+// the math.  There is one barrier per stage, placed between the two 16-MFMA halves of the stage.
+//
+// Instruction order.  A global load costs the wavefront that issues it roughly 75 cycles in which
+// it issues no matrix instruction (measured; the same for loads into registers), and a burst of
+// loads costs the sum.  So the loop body is written as single pieces (one matrix instruction, one
+// fragment read, one direct load) separated by scheduling fences, with the loads of a stage spread
+// evenly over the two halves that follow the barrier which frees their slot.  A further variant
+// (256 x 192, 512 threads) takes the loads out of the math wavefronts altogether: four wavefronts
+// only fetch, four only compute (128 x 96 each, which is what fits the 256 registers a wavefront
+// has at two wavefronts per SIMD).
 //
 // Operand layouts.  Either operand may be stored with K contiguous ("K-major": A as [M,K], B as
 // [N,K]) or with its M/N dimension contiguous ("MN-major": A as [K,M], B as [K,N]).  K-major tiles
@@ -26,6 +34,7 @@
 // epilogue (bias, residual, GeLU input, output) is a 16-byte access and 16 lanes cover 256
 // contiguous bytes of a row.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 #include <cstdlib>
 
@@ -141,19 +150,6 @@ __device__ __forceinline__ void dma_offsets(unsigned (&off)[T], bool (&mn_ok)[T]
     }
 }
 
-// Stage starting at k0; k >= kend is zero filled.
-template <bool KMAJ, int T>
-__device__ __forceinline__ void dma_issue(i32x4 rsrc, unsigned tile_lds, const unsigned (&off)[T],
-                                          const bool (&mn_ok)[T], int kcol, int ld, int k0, int kend, int wave) {
-    const unsigned step = KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * ld * 2);
-#pragma unroll
-    for (int j = 0; j < T; ++j) {
-        bool ok = KMAJ ? (k0 + kcol < kend) : (mn_ok[j] && k0 < kend);
-        unsigned o = ok ? off[j] + step : OOB_OFFSET;
-        buffer_load_lds_b128(rsrc, tile_lds + (wave * T + j) * 1024, o);
-    }
-}
-
 // LDS -> MFMA fragment: rows mn_base + (lane % 32), k = ks*16 + 8*(lane/32) + 0..7.
 template <bool KMAJ, int R>
 __device__ __forceinline__ bf16x8 dma_frag(const char* tile, int mn_base, int ks, int lane) {
@@ -224,22 +220,19 @@ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, 
     tn = within / rows;
 }
 
-template <typename TL, bool A_KMAJ, bool B_KMAJ>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
+template <typename TL, bool A_KMAJ, bool B_KMAJ, bool SPEC>
+__global__ __launch_bounds__(SPEC ? 512 : 256) void gemm_bf16_kernel(GemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TM = TL::TM, TN = TL::TN, BM = TL::BM, BN = TL::BN, DSTAGES = TL::STAGES;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave) & 3;     // loader index when specialised
     const int tile = share_of_block(blockIdx.x, gridDim.x);
 
     const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)(A_KMAJ ? p.M : p.K) * p.lda * 2));
     const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
     const unsigned lds0 = (unsigned)(uintptr_t)(lds_void_ptr)smem;
-    // per half stage: NM MFMAs, NR LDS reads of the next fragment set, TM+TN direct loads (second half)
-    constexpr int NM = TM * TN;
-    constexpr int NR = (A_KMAJ ? TM : 2 * TM) + (B_KMAJ ? TN : 2 * TN);
-    constexpr int RPM = (NR + NM - 2) / (NM - 1);                 // LDS reads placed after each MFMA
+    constexpr int NM = TM * TN;                                   // matrix instructions per half stage
 
     int tm, tn;
     tile_coords(tile, p.tiles_m, p.tiles_n, tm, tn);
@@ -256,66 +249,160 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     unsigned offa[TM], offb[TN];
     bool oka[TM], okb[TN];
     int kca, kcb;
-    dma_offsets<A_KMAJ, TM>(offa, oka, kca, p.lda, m0, p.M, wave, lane);
-    dma_offsets<B_KMAJ, TN>(offb, okb, kcb, p.ldb, n0, p.N, wave, lane);
+    dma_offsets<A_KMAJ, TM>(offa, oka, kca, p.lda, m0, p.M, wave & 3, lane);
+    dma_offsets<B_KMAJ, TN>(offb, okb, kcb, p.ldb, n0, p.N, wave & 3, lane);
 
-    // ring slot of stage s is s % STAGES; stages past the end of K are issued too (all chunks out of
-    // bounds: zero fill, no memory traffic) so the number of loads in flight never changes.
-    auto issue = [&](int s) {
+    // Ring slot of stage s is s % STAGES.  Stages past the end of K are issued too (all chunks out of
+    // bounds: zero fill, no memory traffic) so the number of loads in flight never changes.  The loads
+    // of a stage are numbered 0..LOADS-1 (A chunks, then B chunks); every piece of the loop body below
+    // is fenced so that the instruction order is the one written: one fragment read or one direct
+    // load between matrix instructions, never a burst that fills the memory queue and holds up the
+    // wavefront's next matrix instruction.
+    constexpr int L = TL::LOADS, L1 = L / 2;                     // part 1: loads [0,L1), part 2: [L1,L)
+    auto dma_one = [&](int s, int d) {
         const unsigned buf = lds0 + (s % DSTAGES) * TL::STAGE_BYTES;
-        dma_issue<A_KMAJ, TM>(ra, buf, offa, oka, kca, p.lda, s * DK, p.K, wave_u);
-        dma_issue<B_KMAJ, TN>(rb, buf + TL::A_BYTES, offb, okb, kcb, p.ldb, s * DK, p.K, wave_u);
-    };
-    auto read_frags = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int s, int ks) {
-        const char* buf = smem + (s % DSTAGES) * TL::STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = dma_frag<A_KMAJ, BM>(buf, (wm * TM + i) * 32, ks, lane);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[j] = dma_frag<B_KMAJ, BN>(buf + TL::A_BYTES, (wn * TN + j) * 32, ks, lane);
-    };
-    auto mma = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    };
-
-#pragma unroll
-    for (int s0 = 0; s0 < DSTAGES; ++s0) issue(s0);
-    wait_vmcnt<(DSTAGES - 1) * TL::LOADS>();                     // first stage has landed
-    __builtin_amdgcn_s_barrier();
-    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-    read_frags(fa0, fb0, 0, 0);
-
-    for (int kt = 0; kt < p.nk; ++kt) {
-        // first half: math on k-substep 0 while the fragments of substep 1 are read
-        read_frags(fa1, fb1, kt, 1);
-        mma(fa0, fb0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // math first: no LDS wait at the loop top
-#pragma unroll
-        for (int i = 0; i < NM - 1; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        const int k0 = s * DK;
+        if (d < TM) {
+            bool ok = A_KMAJ ? (k0 + kca < p.K) : (oka[d] && k0 < p.K);
+            unsigned step = A_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.lda * 2);
+            buffer_load_lds_b128(ra, buf + (wave_u * TM + d) * 1024, ok ? offa[d] + step : OOB_OFFSET);
+        } else {
+            const int e = d - TM;
+            bool ok = B_KMAJ ? (k0 + kcb < p.K) : (okb[e] && k0 < p.K);
+            unsigned step = B_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.ldb * 2);
+            buffer_load_lds_b128(rb, buf + TL::A_BYTES + (wave_u * TN + e) * 1024, ok ? offb[e] + step : OOB_OFFSET);
         }
-        // stage kt+1 has landed for this wavefront once only the newer stages are in flight; after the
-        // barrier it has landed for all, and nobody reads stage kt's slot any more.
-        wait_vmcnt<(DSTAGES - 2) * TL::LOADS>();
+    };
+    auto read_one = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], int s, int ks, int r) {
+        const char* buf = smem + (s % DSTAGES) * TL::STAGE_BYTES;
+        if (r < TM) fa[r] = dma_frag<A_KMAJ, BM>(buf, (wm * TM + r) * 32, ks, lane);
+        else fb[r - TM] = dma_frag<B_KMAJ, BN>(buf + TL::A_BYTES, (wn * TN + r - TM) * 32, ks, lane);
+    };
+    // one half stage: NM matrix instructions on (fa, fb); after instruction m, fragment m of the
+    // next set is read, and the direct loads d0..d1-1 of stage ds are spread evenly over the half
+    auto half = [&](const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN], bf16x8 (&na)[TM], bf16x8 (&nb)[TN],
+                    int rs, int rks, int ds, auto d0c, auto d1c) {
+        constexpr int D0 = decltype(d0c)::value, D1 = decltype(d1c)::value, NL = D1 - D0;
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            acc[m / TN][m % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m / TN], fb[m % TN], acc[m / TN][m % TN], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (m < TM + TN) {
+                read_one(na, nb, rs, rks, m);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int d = 0; d < NL; ++d)
+                if (m == ((2 * d + 1) * NM) / (2 * NL)) {
+                    dma_one(ds, D0 + d);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        }
+    };
+    using IC0 = std::integral_constant<int, 0>;
+    using ICL1 = std::integral_constant<int, L1>;
+    using ICL = std::integral_constant<int, L>;
+
+    if constexpr (SPEC) {
+        // Wavefronts 4..7 only fetch, wavefronts 0..3 only compute: a global load holds up the issuing
+        // wavefront's next matrix instruction for tens of cycles, so the loads are taken out of the
+        // math wavefronts' instruction streams altogether.  Both roles meet at the same barriers: one
+        // before the loop, one per stage, one after.
+        if (wave >= 4) {
+#pragma unroll
+            for (int s0 = 0; s0 < DSTAGES; ++s0)
+#pragma unroll
+                for (int d = 0; d < L; ++d) dma_one(s0, d);
+            wait_vmcnt<(DSTAGES - 1) * L>();
+            __builtin_amdgcn_s_barrier();
+            for (int kt = 0; kt < p.nk; ++kt) {
+                wait_vmcnt<(DSTAGES - 2) * L>();                 // stage kt+1 has landed
+                __builtin_amdgcn_s_barrier();                    // ... and stage kt's slot is free
+#pragma unroll
+                for (int d = 0; d < L; ++d) dma_one(kt + DSTAGES, d);
+            }
+            wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            return;
+        }
+        // Registers: the accumulators take 3/4 of a wavefront's budget here, so only the B fragments
+        // and the last A fragment are double buffered; A fragment i < TM-1 of the next k-substep is
+        // read into the registers of the current one as soon as row i's matrix instructions are issued.
+        bf16x8 fa[TM - 1], fal[2], fb[2][TN];
+        auto rd_a = [&](bf16x8& dst, int s, int ks, int i) {
+            const char* buf = smem + (s % DSTAGES) * TL::STAGE_BYTES;
+            dst = dma_frag<A_KMAJ, BM>(buf, (wm * TM + i) * 32, ks, lane);
+        };
+        auto rd_b = [&](bf16x8& dst, int s, int ks, int j) {
+            const char* buf = smem + (s % DSTAGES) * TL::STAGE_BYTES + TL::A_BYTES;
+            dst = dma_frag<B_KMAJ, BN>(buf, (wn * TN + j) * 32, ks, lane);
+        };
+        auto mhalf = [&](auto curc, int rs, int rks) {
+            constexpr int CUR = decltype(curc)::value, NXT = CUR ^ 1;
+            int free_rd = 0;                                     // next of: nb[0..TN-1], last A fragment
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                const int i = m / TN, j = m % TN;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(i < TM - 1 ? fa[i] : fal[CUR], fb[CUR][j], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (j == TN - 1 && i < TM - 1) {
+                    rd_a(fa[i], rs, rks, i);                     // row i is done: refill in place
+                    __builtin_amdgcn_sched_barrier(0);
+                } else if (free_rd <= TN) {
+                    if (free_rd < TN) rd_b(fb[NXT][free_rd], rs, rks, free_rd);
+                    else rd_a(fal[NXT], rs, rks, TM - 1);
+                    ++free_rd;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        };
+        using C0 = std::integral_constant<int, 0>;
+        using C1 = std::integral_constant<int, 1>;
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int i = 0; i < TM - 1; ++i) rd_a(fa[i], 0, 0, i);
+        rd_a(fal[0], 0, 0, TM - 1);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) rd_b(fb[0][j], 0, 0, j);
+        __builtin_amdgcn_sched_barrier(0);
+        for (int kt = 0; kt < p.nk; ++kt) {
+            mhalf(C0{}, kt, 1);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            mhalf(C1{}, kt + 1, 0);
+        }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        issue(kt + DSTAGES);
-        read_frags(fa0, fb0, kt + 1, 0);
-        mma(fa1, fb1);
+    } else {
 #pragma unroll
-        for (int i = 0; i < NM; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, RPM, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        }
+    for (int s0 = 0; s0 < DSTAGES - 1; ++s0)
+#pragma unroll
+        for (int d = 0; d < L; ++d) dma_one(s0, d);
+#pragma unroll
+    for (int d = 0; d < L1; ++d) dma_one(DSTAGES - 1, d);
+    wait_vmcnt<(DSTAGES - 2) * L + L1>();                        // first stage has landed
+    __builtin_amdgcn_s_barrier();
+    bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+#pragma unroll
+    for (int r = 0; r < TM + TN; ++r) read_one(fa0, fb0, 0, 0, r);
+    __builtin_amdgcn_sched_barrier(0);
+
+    for (int kt = 0; kt < p.nk; ++kt) {
+        // first half: math on k-substep 0, fragments of substep 1 are read, rest of stage kt+STAGES-1 is fetched
+        half(fa0, fb0, fa1, fb1, kt, 1, kt + DSTAGES - 1, ICL1{}, ICL{});
+        // stage kt+1 has landed for this wavefront once only the newer stages are in flight; after the
+        // barrier it has landed for all, and nobody reads stage kt's slot any more.
+        wait_vmcnt<(DSTAGES - 2) * L>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        half(fa1, fb1, fa0, fb0, kt + 1, 0, kt + DSTAGES, IC0{}, ICL1{});
     }
     wait_vmcnt<0>();                                             // drain the ring before LDS is reused
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
+    }
 
     // ---- epilogue: accumulators -> per-wavefront LDS staging -> 16-byte row accesses --------------
     constexpr int LPR = TN * 4;               // lanes per staged row (8 columns each)
@@ -380,29 +467,29 @@ bool gemm_bf16_supported(const GemmArgs& a) {
 
 size_t gemm_bf16_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
 
-template <typename TL, bool AK, bool BK_>
+template <typename TL, bool AK, bool BK_, bool SPEC = false>
 static hipError_t launch(GemmParams p, const GemmArgs& a) {
     static bool attr_set = false;   // raising the dynamic LDS limit is a per-function, one-off call
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<TL, AK, BK_>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<TL, AK, BK_, SPEC>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     p.tiles_m = (int)((a.M + TL::BM - 1) / TL::BM);
     p.tiles_n = (int)((a.N + TL::BN - 1) / TL::BN);
-    hipLaunchKernelGGL((gemm_bf16_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n), dim3(256),
+    hipLaunchKernelGGL((gemm_bf16_kernel<TL, AK, BK_, SPEC>), dim3(p.tiles_m * p.tiles_n), dim3(SPEC ? 512 : 256),
                        TL::LDS_BYTES, a.stream, p);
     return hipGetLastError();
 }
 
-template <typename TL>
+template <typename TL, bool SPEC = false>
 static hipError_t launch_layout(const GemmParams& p, const GemmArgs& a) {
     const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
-    if (a_kmaj && b_kmaj) return launch<TL, true, true>(p, a);
-    if (a_kmaj && !b_kmaj) return launch<TL, true, false>(p, a);
-    if (!a_kmaj && b_kmaj) return launch<TL, false, true>(p, a);
-    return launch<TL, false, false>(p, a);
+    if (a_kmaj && b_kmaj) return launch<TL, true, true, SPEC>(p, a);
+    if (a_kmaj && !b_kmaj) return launch<TL, true, false, SPEC>(p, a);
+    if (!a_kmaj && b_kmaj) return launch<TL, false, true, SPEC>(p, a);
+    return launch<TL, false, false, SPEC>(p, a);
 }
 
 // Tile variants.  The host launches the one with the least estimated time
@@ -424,10 +511,10 @@ static int compute_units() {
     return cus;
 }
 
-constexpr int NVARIANTS = 4;
+constexpr int NVARIANTS = 4;   // picked by estimate; variant 4 (specialised wavefronts) by override only
 static int pick_variant(int64_t M, int64_t N, int64_t K) {
     const char* e = getenv("TPL_GEMM_TILE");          // tuning / test override: one digit
-    if (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) return e[0] - '0';
+    if (e && e[0] >= '0' && e[0] <= '4') return e[0] - '0';
     static const int bm[NVARIANTS] = {256, 256, 128, 192}, bn[NVARIANTS] = {256, 192, 128, 192};
     static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2};
     static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576};
@@ -456,6 +543,7 @@ hipError_t gemm_bf16(const GemmArgs& a) {
     p.tiles_m = p.tiles_n = 0;
     p.nk = (int)((a.K + DK - 1) / DK);
     switch (pick_variant(a.M, a.N, a.K)) {
+        case 4: return launch_layout<Tile<4, 3, 4>, true>(p, a);   // specialised 256 x 192
         case 1: return launch_layout<Tile<4, 3, 4>>(p, a);    // 256 x 192
         case 2: return launch_layout<Tile<2, 2, 4>>(p, a);    // 128 x 128, two workgroups per CU
         case 3: return launch_layout<Tile<3, 3, 3>>(p, a);    // 192 x 192, two workgroups per CU

@@ -25,7 +25,7 @@ GEMM_SHAPES = [(256, 256, 64), (520, 264, 136), (1000, 776, 2056), (64, 1536, 40
 
 # bf16 runs once per tile variant of the MFMA kernel (forced through TPL_GEMM_TILE) and once with the
 # library's own choice; float has a single kernel.
-@pytest.mark.parametrize("dtype,tile", [("bf16", None), ("bf16", "0"), ("bf16", "1"), ("bf16", "2"), ("bf16", "3"), ("f32", None)])
+@pytest.mark.parametrize("dtype,tile", [("bf16", None), ("bf16", "0"), ("bf16", "1"), ("bf16", "2"), ("bf16", "3"), ("bf16", "4"), ("f32", None)])
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("epi", ["none", "bias", "bias_resid", "gelu", "dgelu"])
 def test_gemm_variants(dtype, tile, ta, tb, epi, monkeypatch):
