@@ -220,13 +220,70 @@ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, 
     tn = within / rows;
 }
 
-template <typename TL, bool A_KMAJ, bool B_KMAJ, bool SPEC>
-__global__ __launch_bounds__(SPEC ? 512 : 256) void gemm_bf16_kernel(GemmParams p) {
+// Epilogue of one wavefront: accumulators -> its LDS staging area -> 16-byte row accesses.
+template <typename TL>
+__device__ __forceinline__ void epilogue(const GemmParams& p, const f32x16 (&acc)[TL::TM][TL::TN], char* smem,
+                                         int wave, int lane, int m0, int n0) {
+    constexpr int TM = TL::TM, TN = TL::TN;
+    const int wm = wave >> 1, wn = wave & 1;
+    constexpr int LPR = TN * 4;               // lanes per staged row (8 columns each)
+    constexpr int RPP = 64 / LPR;             // rows per pass (lanes beyond RPP*LPR idle when TN = 3)
+    constexpr int PASSES = (32 + RPP - 1) / RPP;
+    char* stage = smem + wave * TL::EWAVE;
+    const int er = lane / LPR, ec = (lane % LPR) * 8;
+    const int gn = n0 + wn * TN * 32 + ec;
+    float bias8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (p.bias && gn < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + gn), bias8);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        // accumulator register v of block (i,j): row (v/4)*8 + (lane/32)*4 + v%4, column j*32 + lane%32
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+                *reinterpret_cast<float*>(stage + row * TL::EROW + (j * 32 + (lane & 31)) * 4) = acc[i][j][v];
+            }
+#pragma unroll
+        for (int pass = 0; pass < PASSES; ++pass) {
+            const int row = pass * RPP + er;
+            const int gm = m0 + (wm * TM + i) * 32 + row;
+            if (er < RPP && row < 32 && gm < p.M && gn < p.N) {
+                const float4* src = reinterpret_cast<const float4*>(stage + row * TL::EROW + ec * 4);
+                float4 x0 = src[0], x1 = src[1];
+                float v8[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+                const int64_t idx = (int64_t)gm * p.N + gn;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v8[e] += bias8[e];
+                if (p.resid) {
+                    float r8[8];
+                    unpack8(*reinterpret_cast<const uint4*>(p.resid + idx), r8);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v8[e] += r8[e];
+                }
+                if (p.epi == EPI_GELU) {
+                    *reinterpret_cast<uint4*>(p.aux + idx) = pack8(v8);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v8[e] = gelu_f(v8[e]);
+                } else if (p.epi == EPI_DGELU) {
+                    float u8[8];
+                    unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), u8);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v8[e] *= gelu_grad_f(u8[e]);
+                }
+                *reinterpret_cast<uint4*>(p.C + idx) = pack8(v8);
+            }
+        }
+    }
+}
+
+template <typename TL, bool A_KMAJ, bool B_KMAJ>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TM = TL::TM, TN = TL::TN, BM = TL::BM, BN = TL::BN, DSTAGES = TL::STAGES;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave) & 3;     // loader index when specialised
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const int tile = share_of_block(blockIdx.x, gridDim.x);
 
     const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)(A_KMAJ ? p.M : p.K) * p.lda * 2));
@@ -249,8 +306,8 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void gemm_bf16_kernel(GemmParams 
     unsigned offa[TM], offb[TN];
     bool oka[TM], okb[TN];
     int kca, kcb;
-    dma_offsets<A_KMAJ, TM>(offa, oka, kca, p.lda, m0, p.M, wave & 3, lane);
-    dma_offsets<B_KMAJ, TN>(offb, okb, kcb, p.ldb, n0, p.N, wave & 3, lane);
+    dma_offsets<A_KMAJ, TM>(offa, oka, kca, p.lda, m0, p.M, wave, lane);
+    dma_offsets<B_KMAJ, TN>(offb, okb, kcb, p.ldb, n0, p.N, wave, lane);
 
     // Ring slot of stage s is s % STAGES.  Stages past the end of K are issued too (all chunks out of
     // bounds: zero fill, no memory traffic) so the number of loads in flight never changes.  The loads
@@ -303,78 +360,6 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void gemm_bf16_kernel(GemmParams 
     using ICL1 = std::integral_constant<int, L1>;
     using ICL = std::integral_constant<int, L>;
 
-    if constexpr (SPEC) {
-        // Wavefronts 4..7 only fetch, wavefronts 0..3 only compute: a global load holds up the issuing
-        // wavefront's next matrix instruction for tens of cycles, so the loads are taken out of the
-        // math wavefronts' instruction streams altogether.  Both roles meet at the same barriers: one
-        // before the loop, one per stage, one after.
-        if (wave >= 4) {
-#pragma unroll
-            for (int s0 = 0; s0 < DSTAGES; ++s0)
-#pragma unroll
-                for (int d = 0; d < L; ++d) dma_one(s0, d);
-            wait_vmcnt<(DSTAGES - 1) * L>();
-            __builtin_amdgcn_s_barrier();
-            for (int kt = 0; kt < p.nk; ++kt) {
-                wait_vmcnt<(DSTAGES - 2) * L>();                 // stage kt+1 has landed
-                __builtin_amdgcn_s_barrier();                    // ... and stage kt's slot is free
-#pragma unroll
-                for (int d = 0; d < L; ++d) dma_one(kt + DSTAGES, d);
-            }
-            wait_vmcnt<0>();
-            __builtin_amdgcn_s_barrier();
-            return;
-        }
-        // Registers: the accumulators take 3/4 of a wavefront's budget here, so only the B fragments
-        // and the last A fragment are double buffered; A fragment i < TM-1 of the next k-substep is
-        // read into the registers of the current one as soon as row i's matrix instructions are issued.
-        bf16x8 fa[TM - 1], fal[2], fb[2][TN];
-        auto rd_a = [&](bf16x8& dst, int s, int ks, int i) {
-            const char* buf = smem + (s % DSTAGES) * TL::STAGE_BYTES;
-            dst = dma_frag<A_KMAJ, BM>(buf, (wm * TM + i) * 32, ks, lane);
-        };
-        auto rd_b = [&](bf16x8& dst, int s, int ks, int j) {
-            const char* buf = smem + (s % DSTAGES) * TL::STAGE_BYTES + TL::A_BYTES;
-            dst = dma_frag<B_KMAJ, BN>(buf, (wn * TN + j) * 32, ks, lane);
-        };
-        auto mhalf = [&](auto curc, int rs, int rks) {
-            constexpr int CUR = decltype(curc)::value, NXT = CUR ^ 1;
-            int free_rd = 0;                                     // next of: nb[0..TN-1], last A fragment
-#pragma unroll
-            for (int m = 0; m < NM; ++m) {
-                const int i = m / TN, j = m % TN;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(i < TM - 1 ? fa[i] : fal[CUR], fb[CUR][j], acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                if (j == TN - 1 && i < TM - 1) {
-                    rd_a(fa[i], rs, rks, i);                     // row i is done: refill in place
-                    __builtin_amdgcn_sched_barrier(0);
-                } else if (free_rd <= TN) {
-                    if (free_rd < TN) rd_b(fb[NXT][free_rd], rs, rks, free_rd);
-                    else rd_a(fal[NXT], rs, rks, TM - 1);
-                    ++free_rd;
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        };
-        using C0 = std::integral_constant<int, 0>;
-        using C1 = std::integral_constant<int, 1>;
-        __builtin_amdgcn_s_barrier();
-#pragma unroll
-        for (int i = 0; i < TM - 1; ++i) rd_a(fa[i], 0, 0, i);
-        rd_a(fal[0], 0, 0, TM - 1);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) rd_b(fb[0][j], 0, 0, j);
-        __builtin_amdgcn_sched_barrier(0);
-        for (int kt = 0; kt < p.nk; ++kt) {
-            mhalf(C0{}, kt, 1);
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            mhalf(C1{}, kt + 1, 0);
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-    } else {
 #pragma unroll
     for (int s0 = 0; s0 < DSTAGES - 1; ++s0)
 #pragma unroll
@@ -402,59 +387,216 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void gemm_bf16_kernel(GemmParams 
     wait_vmcnt<0>();                                             // drain the ring before LDS is reused
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
+    epilogue<TL>(p, acc, smem, wave, lane, m0, n0);
+}
+
+// =================================================================================================
+// Variant with specialised wavefronts: 512 threads, wavefronts 0..3 only compute (2 x 2, each
+// TM x TN blocks), wavefronts 4..7 only fetch.  Both roles meet at the same barriers: one before the
+// loop, one per k-step of 32, one after.
+//
+// LDS rings.  B lives in a ring of NB slots of 32 k.  A K-major A lives in a ring of 3 slots of 64 k
+// (rows of 128 bytes): a direct load then covers 8 whole 128-byte lines instead of 16 half lines,
+// which the vector memory path serves about 1.4 times faster (measured), and global->LDS
+// throughput is what bounds this kernel once the loads no longer hold up matrix instructions.
+// (B stays at 32 k: three 64-k slots of both operands do not fit in 160 KiB.)  An MN-major A uses
+// a ring of NB slots of 32 k like B.  Slot of k-step kt: B kt % NB; wide A (kt / 2) % 3.
+//
+// Fetch order.  After the barrier of k-step kt the B slot of kt is free and is refilled with k-step
+// kt + NB.  A wide A slot (unit u = k-steps 2u, 2u+1) is free after the barrier of k-step 2u+1; unit
+// u+3 is fetched in two halves, after that barrier and after the next one, so every k-step issues
+// TM + TN loads per fetching wavefront.
+// =================================================================================================
+template <int TM_, int TN_>
+struct SpecTile {
+    static constexpr int TM = TM_, TN = TN_, BM = 64 * TM, BN = 64 * TN;
+    static constexpr int NB = 5, NA_WIDE = 3;
+    static constexpr int B_SLOT = BN * DK * 2;                           // 32 k of B
+    static constexpr int A_SLOT32 = BM * DK * 2, A_SLOT64 = BM * 64 * 2;
+    static constexpr int EROW = TN * 32 * 4 + 16, EWAVE = 32 * EROW;     // epilogue staging, as in Tile
+    template <bool A_KMAJ> static constexpr int a_bytes() { return A_KMAJ ? NA_WIDE * A_SLOT64 : NB * A_SLOT32; }
+    template <bool A_KMAJ> static constexpr int lds_bytes() {
+        return a_bytes<A_KMAJ>() + NB * B_SLOT > 4 * EWAVE ? a_bytes<A_KMAJ>() + NB * B_SLOT : 4 * EWAVE;
+    }
+};
+
+// K-major tile with rows of 128 bytes (64 k): 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7),
+// so the 16 rows a quarter-wavefront reads at one k are spread over all banks.
+__device__ __forceinline__ int swz_k64(int row) { return (row >> 1) & 7; }
+__device__ __forceinline__ bf16x8 wide_frag(const char* tile, int mn_base, int k16, int lane) {
+    int row = mn_base + (lane & 31);
+    int c = 2 * k16 + (lane >> 5);
+    return *reinterpret_cast<const bf16x8*>(tile + row * 128 + ((c ^ swz_k64(row)) << 4));
+}
+
+template <typename ST, bool A_KMAJ, bool B_KMAJ>
+__global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int TM = ST::TM, TN = ST::TN, BM = ST::BM, BN = ST::BN, NB = ST::NB, NAW = ST::NA_WIDE;
+    constexpr bool WIDE = A_KMAJ;
+    constexpr int A_BYTES = ST::template a_bytes<A_KMAJ>();
+    constexpr int LPS = TM + TN;                                  // loads per k-step and fetching wavefront
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int tile = share_of_block(blockIdx.x, gridDim.x);
+    int tm, tn;
+    tile_coords(tile, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    if (wave >= 4) {
+        // ---------------- fetching wavefronts ----------------
+        const int w = __builtin_amdgcn_readfirstlane(wave) & 3;
+        const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)(A_KMAJ ? p.M : p.K) * p.lda * 2));
+        const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
+        const unsigned lds_a = (unsigned)(uintptr_t)(lds_void_ptr)smem, lds_b = lds_a + A_BYTES;
+        // B and narrow A: as in the kernel above
+        unsigned offb[TN], offa[TM];
+        bool okb[TN], oka[TM];
+        int kcb, kca = 0;
+        dma_offsets<B_KMAJ, TN>(offb, okb, kcb, p.ldb, n0, p.N, w, lane);
+        // wide A: load q (0 .. 2 TM - 1) of a unit covers rows 8 (2 TM w + q) .. + 7, lane l the chunk at
+        // LDS position l % 8 of row l / 8
+        unsigned offw[2 * TM];
+        int kcw[2 * TM];
+        if (WIDE) {
+#pragma unroll
+            for (int q = 0; q < 2 * TM; ++q) {
+                int row = (w * 2 * TM + q) * 8 + (lane >> 3);
+                int c = (lane & 7) ^ swz_k64(row);
+                kcw[q] = c * 8;
+                offw[q] = (unsigned)(((int64_t)(m0 + row) * p.lda + c * 8) * 2);
+            }
+        } else {
+            dma_offsets<A_KMAJ, TM>(offa, oka, kca, p.lda, m0, p.M, w, lane);
+        }
+        auto load_b = [&](int kt) {                               // k-step kt of B into its slot
+            const unsigned buf = lds_b + (kt % NB) * ST::B_SLOT;
+            const int k0 = kt * DK;
+            const unsigned step = B_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.ldb * 2);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                bool ok = B_KMAJ ? (k0 + kcb < p.K) : (okb[j] && k0 < p.K);
+                buffer_load_lds_b128(rb, buf + (w * TN + j) * 1024, ok ? offb[j] + step : OOB_OFFSET);
+            }
+        };
+        auto load_a32 = [&](int kt) {
+            const unsigned buf = lds_a + (kt % NB) * ST::A_SLOT32;
+            const int k0 = kt * DK;
+            const unsigned step = A_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.lda * 2);
+#pragma unroll
+            for (int j = 0; j < TM; ++j) {
+                bool ok = A_KMAJ ? (k0 + kca < p.K) : (oka[j] && k0 < p.K);
+                buffer_load_lds_b128(ra, buf + (w * TM + j) * 1024, ok ? offa[j] + step : OOB_OFFSET);
+            }
+        };
+        auto load_a64 = [&](int u, int half) {                    // half 0/1 of unit u (k = 64 u ..)
+            const unsigned buf = lds_a + (u % NAW) * ST::A_SLOT64;
+#pragma unroll
+            for (int q = half * TM; q < (half + 1) * TM; ++q)
+                buffer_load_lds_b128(ra, buf + (w * 2 * TM + q) * 1024,
+                                     64 * u + kcw[q] < p.K ? offw[q] + (unsigned)u * 128u : OOB_OFFSET);
+        };
+        // prologue: everything the rings hold, except the second half of the last wide unit
+        if (WIDE) {
+            load_a64(0, 0); load_a64(0, 1); load_b(0);
+            load_a64(1, 0); load_a64(1, 1); load_a64(2, 0);
+#pragma unroll
+            for (int s0 = 1; s0 < NB; ++s0) load_b(s0);
+            wait_vmcnt<3 * TM + (NB - 1) * TN>();                 // unit 0 and B step 0 have landed
+        } else {
+            load_a32(0); load_b(0);
+#pragma unroll
+            for (int s0 = 1; s0 < NB; ++s0) { load_a32(s0); load_b(s0); }
+            wait_vmcnt<(NB - 1) * LPS>();
+        }
+        __builtin_amdgcn_s_barrier();
+        // Loads in flight allowed at the barrier of k-step kt (k-step kt+1 must have landed).  B step
+        // kt+1 went out as the last loads of k-step kt+1-NB; the second half of a wide unit that starts
+        // at kt+1 went out as the first loads of k-step kt-3.
+        constexpr int W_B = (NB - 2) * LPS;
+        constexpr int W_A = WIDE ? TN + 2 * LPS : TN + (NB - 2) * LPS;
+        constexpr int W = W_A < W_B ? W_A : W_B;
+        for (int kt = 0; kt < p.nk; ++kt) {
+            // The first two k-steps of a wide A come straight after the prologue, which ends with the
+            // B steps: fewer loads follow the ones needed than in the steady state.
+            if (WIDE && kt == 0) wait_vmcnt<(NB - 2) * TN>();                  // B step 1
+            else if (WIDE && kt == 1) wait_vmcnt<(NB - 3) * TN + LPS>();       // unit 1, B step 2
+            else wait_vmcnt<W>();
+            __builtin_amdgcn_s_barrier();                         // k-step kt has been read by everyone
+            if (WIDE) {
+                // odd kt = 2u+1 frees unit u: first half of unit u+3; even kt = 2u+2: its second half
+                if (kt & 1) load_a64((kt >> 1) + 3, 0);
+                else load_a64((kt >> 1) + 2, 1);
+            } else {
+                load_a32(kt + NB);
+            }
+            load_b(kt + NB);
+        }
+        wait_vmcnt<0>();                                          // nothing lands in LDS during the epilogue
+        __builtin_amdgcn_s_barrier();
+        return;
     }
 
-    // ---- epilogue: accumulators -> per-wavefront LDS staging -> 16-byte row accesses --------------
-    constexpr int LPR = TN * 4;               // lanes per staged row (8 columns each)
-    constexpr int RPP = 64 / LPR;             // rows per pass (lanes beyond RPP*LPR idle when TN = 3)
-    constexpr int PASSES = (32 + RPP - 1) / RPP;
-    char* stage = smem + wave * TL::EWAVE;
-    const int er = lane / LPR, ec = (lane % LPR) * 8;
-    const int gn = n0 + wn * TN * 32 + ec;
-    float bias8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (p.bias && gn < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + gn), bias8);
+    // ---------------- math wavefronts ----------------
+    const int wm = wave >> 1, wn = wave & 1;
+    constexpr int NM = TM * TN;
+    f32x16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        // accumulator register v of block (i,j): row (v/4)*8 + (lane/32)*4 + v%4, column j*32 + lane%32
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int row = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                *reinterpret_cast<float*>(stage + row * TL::EROW + (j * 32 + (lane & 31)) * 4) = acc[i][j][v];
-            }
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    // Registers: the accumulators take 3/4 of a wavefront's budget (two wavefronts per SIMD), so only
+    // the B fragments and the last A fragment are double buffered; A fragment i < TM-1 of the next
+    // k-substep is read into the registers of the current one once row i's matrix instructions are issued.
+    bf16x8 fa[TM - 1], fal[2], fb[2][TN];
+    auto rd_a = [&](bf16x8& dst, int kt, int ks, int i) {         // k-substep ks (16 k) of k-step kt
+        if (WIDE) dst = wide_frag(smem + ((kt >> 1) % NAW) * ST::A_SLOT64, (wm * TM + i) * 32, (kt & 1) * 2 + ks, lane);
+        else dst = dma_frag<A_KMAJ, BM>(smem + (kt % NB) * ST::A_SLOT32, (wm * TM + i) * 32, ks, lane);
+    };
+    auto rd_b = [&](bf16x8& dst, int kt, int ks, int j) {
+        dst = dma_frag<B_KMAJ, BN>(smem + A_BYTES + (kt % NB) * ST::B_SLOT, (wn * TN + j) * 32, ks, lane);
+    };
+    auto mhalf = [&](auto curc, int rkt, int rks) {
+        constexpr int CUR = decltype(curc)::value, NXT = CUR ^ 1;
+        int free_rd = 0;                                          // next of: B fragments 0..TN-1, last A fragment
 #pragma unroll
-        for (int pass = 0; pass < PASSES; ++pass) {
-            const int row = pass * RPP + er;
-            const int gm = m0 + (wm * TM + i) * 32 + row;
-            if (er < RPP && row < 32 && gm < p.M && gn < p.N) {
-                const float4* src = reinterpret_cast<const float4*>(stage + row * TL::EROW + ec * 4);
-                float4 x0 = src[0], x1 = src[1];
-                float v8[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-                const int64_t idx = (int64_t)gm * p.N + gn;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v8[e] += bias8[e];
-                if (p.resid) {
-                    float r8[8];
-                    unpack8(*reinterpret_cast<const uint4*>(p.resid + idx), r8);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v8[e] += r8[e];
-                }
-                if (p.epi == EPI_GELU) {
-                    *reinterpret_cast<uint4*>(p.aux + idx) = pack8(v8);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v8[e] = gelu_f(v8[e]);
-                } else if (p.epi == EPI_DGELU) {
-                    float u8[8];
-                    unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), u8);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v8[e] *= gelu_grad_f(u8[e]);
-                }
-                *reinterpret_cast<uint4*>(p.C + idx) = pack8(v8);
+        for (int m = 0; m < NM; ++m) {
+            const int i = m / TN, j = m % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(i < TM - 1 ? fa[i] : fal[CUR], fb[CUR][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (j == TN - 1 && i < TM - 1) {
+                rd_a(fa[i], rkt, rks, i);                         // row i is done: refill in place
+                __builtin_amdgcn_sched_barrier(0);
+            } else if (free_rd <= TN) {
+                if (free_rd < TN) rd_b(fb[NXT][free_rd], rkt, rks, free_rd);
+                else rd_a(fal[NXT], rkt, rks, TM - 1);
+                ++free_rd;
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+    };
+    using C0 = std::integral_constant<int, 0>;
+    using C1 = std::integral_constant<int, 1>;
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < TM - 1; ++i) rd_a(fa[i], 0, 0, i);
+    rd_a(fal[0], 0, 0, TM - 1);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) rd_b(fb[0][j], 0, 0, j);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int kt = 0; kt < p.nk; ++kt) {
+        mhalf(C0{}, kt, 1);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        mhalf(C1{}, kt + 1, 0);
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    epilogue<ST>(p, acc, smem, wave, lane, m0, n0);
 }
+
 
 bool gemm_bf16_supported(const GemmArgs& a) {
     if (a.dtype != BF16) return false;
@@ -467,29 +609,53 @@ bool gemm_bf16_supported(const GemmArgs& a) {
 
 size_t gemm_bf16_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
 
-template <typename TL, bool AK, bool BK_, bool SPEC = false>
+template <typename TL, bool AK, bool BK_>
 static hipError_t launch(GemmParams p, const GemmArgs& a) {
     static bool attr_set = false;   // raising the dynamic LDS limit is a per-function, one-off call
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<TL, AK, BK_, SPEC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<TL, AK, BK_>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     p.tiles_m = (int)((a.M + TL::BM - 1) / TL::BM);
     p.tiles_n = (int)((a.N + TL::BN - 1) / TL::BN);
-    hipLaunchKernelGGL((gemm_bf16_kernel<TL, AK, BK_, SPEC>), dim3(p.tiles_m * p.tiles_n), dim3(SPEC ? 512 : 256),
+    hipLaunchKernelGGL((gemm_bf16_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n), dim3(256),
                        TL::LDS_BYTES, a.stream, p);
     return hipGetLastError();
 }
 
-template <typename TL, bool SPEC = false>
+template <typename TL>
 static hipError_t launch_layout(const GemmParams& p, const GemmArgs& a) {
     const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
-    if (a_kmaj && b_kmaj) return launch<TL, true, true, SPEC>(p, a);
-    if (a_kmaj && !b_kmaj) return launch<TL, true, false, SPEC>(p, a);
-    if (!a_kmaj && b_kmaj) return launch<TL, false, true, SPEC>(p, a);
-    return launch<TL, false, false, SPEC>(p, a);
+    if (a_kmaj && b_kmaj) return launch<TL, true, true>(p, a);
+    if (a_kmaj && !b_kmaj) return launch<TL, true, false>(p, a);
+    if (!a_kmaj && b_kmaj) return launch<TL, false, true>(p, a);
+    return launch<TL, false, false>(p, a);
+}
+
+template <typename ST, bool AK, bool BK_>
+static hipError_t launch_spec(GemmParams p, const GemmArgs& a) {
+    constexpr int LDS = ST::template lds_bytes<AK>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_spec_kernel<ST, AK, BK_>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    p.tiles_m = (int)((a.M + ST::BM - 1) / ST::BM);
+    p.tiles_n = (int)((a.N + ST::BN - 1) / ST::BN);
+    hipLaunchKernelGGL((gemm_bf16_spec_kernel<ST, AK, BK_>), dim3(p.tiles_m * p.tiles_n), dim3(512), LDS, a.stream, p);
+    return hipGetLastError();
+}
+template <typename ST>
+static hipError_t launch_spec_layout(const GemmParams& p, const GemmArgs& a) {
+    const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
+    if (a_kmaj && b_kmaj) return launch_spec<ST, true, true>(p, a);
+    if (a_kmaj && !b_kmaj) return launch_spec<ST, true, false>(p, a);
+    if (!a_kmaj && b_kmaj) return launch_spec<ST, false, true>(p, a);
+    return launch_spec<ST, false, false>(p, a);
 }
 
 // Tile variants.  The host launches the one with the least estimated time
@@ -511,22 +677,24 @@ static int compute_units() {
     return cus;
 }
 
-constexpr int NVARIANTS = 4;   // picked by estimate; variant 4 (specialised wavefronts) by override only
-static int pick_variant(int64_t M, int64_t N, int64_t K) {
+constexpr int NVARIANTS = 5;
+static int pick_variant(int64_t M, int64_t N, int64_t K, bool a_kmaj) {
     const char* e = getenv("TPL_GEMM_TILE");          // tuning / test override: one digit
-    if (e && e[0] >= '0' && e[0] <= '4') return e[0] - '0';
-    static const int bm[NVARIANTS] = {256, 256, 128, 192}, bn[NVARIANTS] = {256, 192, 128, 192};
-    static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2};
-    static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576};
-    const double fixed_us = 12.0;
+    if (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) return e[0] - '0';
+    static const int bm[NVARIANTS] = {256, 256, 128, 192, 256}, bn[NVARIANTS] = {256, 192, 128, 192, 192};
+    static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2, 1};
+    static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658};
+    static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0};
     const int cus = compute_units();
     const double nk = (double)((K + DK - 1) / DK);
     int best = 0;
     double best_c = 0;
     for (int v = 0; v < NVARIANTS; ++v) {
+        // the variant with fetch-only wavefronts is built for a K-major A (its MN-major A path spills)
+        if (v == 4 && !a_kmaj) continue;
         int64_t tiles = ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]);
         double per_cu = (double)((tiles + cus - 1) / cus);
-        double c = per_cu * nk * us_per_stage[v] + fixed_us * (wgs_per_cu[v] == 1 ? per_cu : 1.0);
+        double c = per_cu * nk * us_per_stage[v] + fixed_us[v] * (wgs_per_cu[v] == 1 ? per_cu : 1.0);
         if (v == 0 || c < best_c) { best = v; best_c = c; }
     }
     return best;
@@ -542,8 +710,8 @@ hipError_t gemm_bf16(const GemmArgs& a) {
     p.epi = a.epi;
     p.tiles_m = p.tiles_n = 0;
     p.nk = (int)((a.K + DK - 1) / DK);
-    switch (pick_variant(a.M, a.N, a.K)) {
-        case 4: return launch_layout<Tile<4, 3, 4>, true>(p, a);   // specialised 256 x 192
+    switch (pick_variant(a.M, a.N, a.K, !a.trans_a)) {
+        case 4: return launch_spec_layout<SpecTile<4, 3>>(p, a);   // 256 x 192, fetch and math wavefronts
         case 1: return launch_layout<Tile<4, 3, 4>>(p, a);    // 256 x 192
         case 2: return launch_layout<Tile<2, 2, 4>>(p, a);    // 128 x 128, two workgroups per CU
         case 3: return launch_layout<Tile<3, 3, 3>>(p, a);    // 192 x 192, two workgroups per CU
