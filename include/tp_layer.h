@@ -169,6 +169,56 @@ int tp_layer_ln_bwd(int dtype, int64_t M, int64_t H, const void* dy, const void*
                     const float* mean, const float* rstd, const void* gamma,
                     void* dz, void* dgamma, void* dbeta, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* Memory-optimised distribution, local compute of one rank (App. F.2): every linear layer is split
+ * over its INPUT channels, its product is a full-width partial sum and a reduce-scatter over the
+ * ranks replaces the all-reduce; layer normalisation is distributed too.  The collectives are the
+ * caller's.  The linear layers themselves are tp_layer_gemm calls on the rank's operands:
+ *   forward  partial[M, N] = x_loc[M, Ks] w_rows[Ks, N]         (trans_a = 0, trans_b = 0, no epilogue)
+ *   backward dx_loc = dy_full w_rows^T (trans_b = 1);  dw_rows = x_loc^T dy_full (trans_a = 1)
+ * with dy_full the all-gathered output gradient; attention on the local heads is tp_layer_attn_*.
+ * The entry points below are the pieces around them.  All tensors device memory, 16-byte aligned;
+ * Hs and N multiples of 8, Hs <= 16384; sums / totals are float [M][2].
+ *
+ * Distributed layer normalisation of the channel slice x_loc [M, Hs] (H channels over all ranks):
+ *   1. tp_layer_ln_moments : sums[m] = (sum_c x_loc[m,c], sum_c x_loc[m,c]^2)
+ *      (the caller all-reduces `sums` over the ranks: two scalars per token)
+ *   2. tp_layer_ln_stats   : mean = S1/H, rstd = 1/sqrt(S2/H - mean^2 + eps) from the totals
+ *   3. tp_layer_ln_apply_fwd ("ApplyLayerNorm"): y = (x_loc - mean) * rstd * gamma_loc + beta_loc
+ * and its backward, xh = (x_loc - mean) * rstd:
+ *   4. tp_layer_ln_apply_bwd_sums : sums[m] = (sum_c dy*gamma_loc, sum_c dy*gamma_loc*xh)   (all-reduced by the caller)
+ *   5. tp_layer_ln_apply_bwd      : dx = rstd * (dy*gamma_loc - C1/H - xh*C2/H) with the totals (C1, C2),
+ *      plus dx_add if it is not NULL (the gradient that reaches x over the residual branch);
+ *      dgamma_loc = sum_m dy*xh, dbeta_loc = sum_m dy (fixed summation order).
+ *      ws_bytes >= tp_layer_ln_apply_workspace_bytes(M, Hs). */
+int tp_layer_ln_moments(int dtype, int64_t M, int64_t Hs, const void* x_loc, float* sums, void* hip_stream);
+int tp_layer_ln_stats(int64_t M, int64_t H, float eps, const float* totals, float* mean, float* rstd,
+                      void* hip_stream);
+int tp_layer_ln_apply_fwd(int dtype, int64_t M, int64_t Hs, const void* x_loc, const float* mean,
+                          const float* rstd, const void* gamma_loc, const void* beta_loc, void* y,
+                          void* hip_stream);
+int tp_layer_ln_apply_bwd_sums(int dtype, int64_t M, int64_t Hs, const void* dy, const void* x_loc,
+                               const float* mean, const float* rstd, const void* gamma_loc, float* sums,
+                               void* hip_stream);
+size_t tp_layer_ln_apply_workspace_bytes(int64_t M, int64_t Hs);
+int tp_layer_ln_apply_bwd(int dtype, int64_t M, int64_t Hs, int64_t H, const void* dy, const void* x_loc,
+                          const float* mean, const float* rstd, const void* gamma_loc, const float* totals,
+                          const void* dx_add, void* dx, void* dgamma_loc, void* dbeta_loc, void* ws,
+                          size_t ws_bytes, void* hip_stream);
+/* What a rank does to the slice [M, N] it keeps after a reduce-scatter (the product of an input-split
+ * linear is a partial sum, so bias, residual and activation cannot ride in the GEMM epilogue):
+ *   forward : v = in + bias (+ resid if resid != NULL);
+ *             TPL_ACT_NONE: out = v;   TPL_ACT_GELU: u = v (kept for backward), out = gelu(v)
+ *   backward: TPL_ACT_GELU: din = dout * gelu'(u);  TPL_ACT_NONE: the gradient of `in` (and of `resid`) is
+ *             dout itself and din is not written (may be NULL);  dbias = sum_m of that gradient (fixed order).
+ * in, resid, u, out, dout, din: [M, N] dtype; bias, dbias: [N] dtype; out may alias in.
+ * ws_bytes >= tp_layer_slice_epilogue_workspace_bytes(M, N). */
+enum { TPL_ACT_NONE = 0, TPL_ACT_GELU = 1 };
+int tp_layer_slice_epilogue_fwd(int dtype, int act, int64_t M, int64_t N, const void* in, const void* bias,
+                                const void* resid, void* u, void* out, void* hip_stream);
+size_t tp_layer_slice_epilogue_workspace_bytes(int64_t M, int64_t N);
+int tp_layer_slice_epilogue_bwd(int dtype, int act, int64_t M, int64_t N, const void* dout, const void* u,
+                                void* din, void* dbias, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* One GEMM of the path with its fused epilogue, exposed for per-kernel tests and timing:
  *   C[M,N] = epi( opA(A) opB(B) ),  element type `dtype`, float accumulation.
  * trans_a == 0: A is [M,K] row-major, else A is [K,M] row-major (used as its transpose).

@@ -22,8 +22,8 @@ only library primitive used as a step.
 
 The paper's figures of this mode are missing from its text, so the order of the
 pieces inside a block is a reading (listed in the design notes): pre-normalised
-blocks, y = x + Block(LN(x)), with the bias of an input-split linear added once,
-after the reduce-scatter, on the slice that owns it.
+blocks, y = x + Block(LN(x)), with the bias of an input-split linear (and the
+residual) added once, after the reduce-scatter, by the rank that keeps that slice.
 
 Pins (tests/test_oracle_memopt.py): moments + ApplyLayerNorm on T slices equals the
 textbook layer normalisation of the full rows (np.mean / np.var) and PyTorch's
@@ -99,16 +99,29 @@ def gelu_grad(u):
     return 0.5 * (1.0 + _erf(u / np.sqrt(2.0))) + u * np.exp(-0.5 * u * u) / np.sqrt(2.0 * np.pi)
 
 
+def slice_epilogue_fwd(part_slice, bias, resid=None, act="none"):
+    """What a rank does to the slice it keeps after a reduce-scatter: v = slice + bias (+ residual);
+    returns (v, gelu(v)) for act == "gelu" (v is kept for the backward) and (None, v) otherwise."""
+    v = np.asarray(part_slice, _F) + np.asarray(bias, _F)
+    if resid is not None:
+        v = v + np.asarray(resid, _F)
+    return (v, gelu(v)) if act == "gelu" else (None, v)
+
+
+def slice_epilogue_bwd(dout, u=None, act="none"):
+    """Gradient of the slice (and of the residual, when act is "none") and of the bias (column sums)."""
+    d = np.asarray(dout, _F) * gelu_grad(u) if act == "gelu" else np.asarray(dout, _F)
+    return d, d.sum(axis=0)
+
+
 def bias_gelu_fwd(u_in, bias):
     """U = u_in + bias (kept for the backward), G = gelu(U)."""
-    u = np.asarray(u_in, _F) + np.asarray(bias, _F)
-    return u, gelu(u)
+    return slice_epilogue_fwd(u_in, bias, None, "gelu")
 
 
 def bias_gelu_bwd(dg, u):
     """dU = dG * gelu'(U); dbias = column sums of dU."""
-    du = np.asarray(dg, _F) * gelu_grad(u)
-    return du, du.sum(axis=0)
+    return slice_epilogue_bwd(dg, u, "gelu")
 
 
 # ---- the collectives (definitions; performed by the caller in a real run) -------------------------
@@ -211,15 +224,15 @@ def memopt_layer_fwd(x_slices, shards, B, S, nl, dh, causal, eps):
 
     h1 = dist_ln(sv["x"], "g1", "b1", "ln1")
     part = [linear_part_fwd(h1[r], shards[r]["w_qkv"]) for r in range(T)]
-    qkv = [reduce_scatter(part, r, T) + shards[r]["b_qkv"] for r in range(T)]
+    qkv = [slice_epilogue_fwd(reduce_scatter(part, r, T), shards[r]["b_qkv"])[1] for r in range(T)]
     att = [_attention(qkv[r], B, S, nl, dh, causal) for r in range(T)]
     part = [linear_part_fwd(att[r][0], shards[r]["w_o"]) for r in range(T)]
-    y1 = [sv["x"][r] + reduce_scatter(part, r, T) + shards[r]["b_o"] for r in range(T)]
+    y1 = [slice_epilogue_fwd(reduce_scatter(part, r, T), shards[r]["b_o"], sv["x"][r])[1] for r in range(T)]
     h2 = dist_ln(y1, "g2", "b2", "ln2")
     part = [linear_part_fwd(h2[r], shards[r]["w_up"]) for r in range(T)]
     ug = [bias_gelu_fwd(reduce_scatter(part, r, T), shards[r]["b_up"]) for r in range(T)]
     part = [linear_part_fwd(ug[r][1], shards[r]["w_dn"]) for r in range(T)]
-    y2 = [y1[r] + reduce_scatter(part, r, T) + shards[r]["b_dn"] for r in range(T)]
+    y2 = [slice_epilogue_fwd(reduce_scatter(part, r, T), shards[r]["b_dn"], y1[r])[1] for r in range(T)]
     sv.update(h1=h1, att=att, y1=y1, h2=h2, ug=ug)
     return y2, sv
 
@@ -246,7 +259,7 @@ def memopt_layer_bwd(dy_slices, shards, sv, B, S, nl, dh):
     full = np.concatenate(dy2, axis=1)                             # all-gather
     dg, dhid = [], []
     for r in range(T):
-        gr[r]["b_dn"] = dy2[r].sum(axis=0)
+        _, gr[r]["b_dn"] = slice_epilogue_bwd(dy2[r])
         d_in, gr[r]["w_dn"] = linear_part_bwd(sv["ug"][r][1], shards[r]["w_dn"], full)
         dg.append(d_in)
     du = []
@@ -262,14 +275,14 @@ def memopt_layer_bwd(dy_slices, shards, sv, B, S, nl, dh):
     full = np.concatenate(dy1, axis=1)
     d_o = []
     for r in range(T):
-        gr[r]["b_o"] = dy1[r].sum(axis=0)
+        _, gr[r]["b_o"] = slice_epilogue_bwd(dy1[r])
         d_in, gr[r]["w_o"] = linear_part_bwd(sv["att"][r][0], shards[r]["w_o"], full)
         d_o.append(d_in)
     dqkv = [_attention_bwd(d_o[r], sv["att"][r][1], B, S, nl, dh) for r in range(T)]
     full = np.concatenate(dqkv, axis=1)
     dh1 = []
     for r in range(T):
-        gr[r]["b_qkv"] = dqkv[r].sum(axis=0)
+        _, gr[r]["b_qkv"] = slice_epilogue_bwd(dqkv[r])
         d_in, gr[r]["w_qkv"] = linear_part_bwd(sv["h1"][r], shards[r]["w_qkv"], full)
         dh1.append(d_in)
     dx = [dy1[r] + v for r, v in enumerate(dist_ln_bwd(dh1, sv["x"], "ln1", "g1", "g1", "b1"))]

@@ -13,6 +13,10 @@ from .binding import (  # noqa: F401
     tp_layer_attn_fwd, tp_layer_attn_bwd, tp_layer_strerror, tp_layer_profile, tp_layer_profile_read,
     tp_layer_workspace_bytes_recompute, tp_layer_bwd_recompute,
     tp_layer_ln_workspace_bytes, tp_layer_ln_fwd, tp_layer_ln_bwd,
+    tp_layer_ln_moments, tp_layer_ln_stats, tp_layer_ln_apply_fwd, tp_layer_ln_apply_bwd_sums,
+    tp_layer_ln_apply_workspace_bytes, tp_layer_ln_apply_bwd,
+    tp_layer_slice_epilogue_fwd, tp_layer_slice_epilogue_workspace_bytes, tp_layer_slice_epilogue_bwd,
+    TPL_ACT_NONE, TPL_ACT_GELU,
 )
 
 

@@ -13,6 +13,7 @@ TPL_OK, TPL_EINVAL, TPL_EUNSUPPORTED, TPL_EWORKSPACE, TPL_EALIGN, TPL_EHIP = ran
 TPL_F32, TPL_BF16 = 0, 1
 TPL_CAUSAL, TPL_ROW_EPILOGUE = 1, 2
 TPL_EPI_NONE, TPL_EPI_GELU, TPL_EPI_DGELU = 0, 1, 2
+TPL_ACT_NONE, TPL_ACT_GELU = 0, 1
 
 _vp = ctypes.c_void_p
 
@@ -77,6 +78,15 @@ def load_library():
         "tp_layer_ln_workspace_bytes": (sz, [i64, i64]),
         "tp_layer_ln_fwd": (ci, [ci, i64, i64, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _vp]),
         "tp_layer_ln_bwd": (ci, [ci, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, sz, _vp]),
+        "tp_layer_ln_moments": (ci, [ci, i64, i64, _vp, _vp, _vp]),
+        "tp_layer_ln_stats": (ci, [i64, i64, ctypes.c_float, _vp, _vp, _vp, _vp]),
+        "tp_layer_ln_apply_fwd": (ci, [ci, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+        "tp_layer_ln_apply_bwd_sums": (ci, [ci, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+        "tp_layer_ln_apply_workspace_bytes": (sz, [i64, i64]),
+        "tp_layer_ln_apply_bwd": (ci, [ci, i64, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, sz, _vp]),
+        "tp_layer_slice_epilogue_fwd": (ci, [ci, ci, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp]),
+        "tp_layer_slice_epilogue_workspace_bytes": (sz, [i64, i64]),
+        "tp_layer_slice_epilogue_bwd": (ci, [ci, ci, i64, i64, _vp, _vp, _vp, _vp, _vp, sz, _vp]),
         "tp_layer_profile": (ci, [ci]),
         "tp_layer_profile_read": (ci, [ctypes.POINTER(ctypes.c_float), ci, ctypes.POINTER(ci)]),
         "tp_layer_strerror": (ctypes.c_char_p, [ci]),
@@ -209,6 +219,64 @@ def tp_layer_ln_bwd(dtype, M, H, dy, z, mean, rstd, gamma, dz, dgamma, dbeta, ws
     if check and rc != TPL_OK:
         raise TpLayerError(rc, "tp_layer_ln_bwd")
     return rc
+
+
+def _checked(rc, what, check):
+    if check and rc != TPL_OK:
+        raise TpLayerError(rc, what)
+    return rc
+
+
+def tp_layer_ln_moments(dtype, M, Hs, x_loc, sums, stream=None, check=True):
+    rc = load_library().tp_layer_ln_moments(dtype, M, Hs, _ptr(x_loc), _ptr(sums), _stream(stream))
+    return _checked(rc, "tp_layer_ln_moments", check)
+
+
+def tp_layer_ln_stats(M, H, eps, totals, mean, rstd, stream=None, check=True):
+    rc = load_library().tp_layer_ln_stats(M, H, float(eps), _ptr(totals), _ptr(mean), _ptr(rstd), _stream(stream))
+    return _checked(rc, "tp_layer_ln_stats", check)
+
+
+def tp_layer_ln_apply_fwd(dtype, M, Hs, x_loc, mean, rstd, gamma_loc, beta_loc, y, stream=None, check=True):
+    rc = load_library().tp_layer_ln_apply_fwd(dtype, M, Hs, _ptr(x_loc), _ptr(mean), _ptr(rstd), _ptr(gamma_loc),
+                                              _ptr(beta_loc), _ptr(y), _stream(stream))
+    return _checked(rc, "tp_layer_ln_apply_fwd", check)
+
+
+def tp_layer_ln_apply_bwd_sums(dtype, M, Hs, dy, x_loc, mean, rstd, gamma_loc, sums, stream=None, check=True):
+    rc = load_library().tp_layer_ln_apply_bwd_sums(dtype, M, Hs, _ptr(dy), _ptr(x_loc), _ptr(mean), _ptr(rstd),
+                                                   _ptr(gamma_loc), _ptr(sums), _stream(stream))
+    return _checked(rc, "tp_layer_ln_apply_bwd_sums", check)
+
+
+def tp_layer_ln_apply_workspace_bytes(M, Hs):
+    return load_library().tp_layer_ln_apply_workspace_bytes(M, Hs)
+
+
+def tp_layer_ln_apply_bwd(dtype, M, Hs, H, dy, x_loc, mean, rstd, gamma_loc, totals, dx_add, dx, dgamma_loc,
+                          dbeta_loc, ws, ws_bytes=None, stream=None, check=True):
+    rc = load_library().tp_layer_ln_apply_bwd(
+        dtype, M, Hs, H, _ptr(dy), _ptr(x_loc), _ptr(mean), _ptr(rstd), _ptr(gamma_loc), _ptr(totals), _ptr(dx_add),
+        _ptr(dx), _ptr(dgamma_loc), _ptr(dbeta_loc), _ptr(ws), (_nbytes(ws) or 0) if ws_bytes is None else ws_bytes,
+        _stream(stream))
+    return _checked(rc, "tp_layer_ln_apply_bwd", check)
+
+
+def tp_layer_slice_epilogue_fwd(dtype, act, M, N, inp, bias, resid, u, out, stream=None, check=True):
+    rc = load_library().tp_layer_slice_epilogue_fwd(dtype, act, M, N, _ptr(inp), _ptr(bias), _ptr(resid), _ptr(u),
+                                                    _ptr(out), _stream(stream))
+    return _checked(rc, "tp_layer_slice_epilogue_fwd", check)
+
+
+def tp_layer_slice_epilogue_workspace_bytes(M, N):
+    return load_library().tp_layer_slice_epilogue_workspace_bytes(M, N)
+
+
+def tp_layer_slice_epilogue_bwd(dtype, act, M, N, dout, u, din, dbias, ws, ws_bytes=None, stream=None, check=True):
+    rc = load_library().tp_layer_slice_epilogue_bwd(dtype, act, M, N, _ptr(dout), _ptr(u), _ptr(din), _ptr(dbias),
+                                                    _ptr(ws), (_nbytes(ws) or 0) if ws_bytes is None else ws_bytes,
+                                                    _stream(stream))
+    return _checked(rc, "tp_layer_slice_epilogue_bwd", check)
 
 
 def tp_layer_profile(enable):

@@ -70,6 +70,24 @@ size_t ln_scratch_bytes(int64_t M, int64_t H);
 hipError_t ln_fwd(const LnArgs& a);
 hipError_t ln_bwd(const LnArgs& a);
 
+// Distributed layer normalisation of a channel slice [M, Hs] (of H channels in all) and bias / residual / GeLU on a
+// slice: the element-wise pieces of the memory-optimised distribution.  sums / totals are [M][2] floats.
+hipError_t ln_dist_moments(int dtype, int64_t M, int64_t Hs, const void* x, float* sums, hipStream_t s);
+hipError_t ln_dist_stats(int64_t M, int64_t H, float eps, const float* totals, float* mean, float* rstd,
+                         hipStream_t s);
+hipError_t ln_dist_apply(int dtype, int64_t M, int64_t Hs, const void* x, const float* mean, const float* rstd,
+                         const void* gamma, const void* beta, void* y, hipStream_t s);
+hipError_t ln_dist_bwd_sums(int dtype, int64_t M, int64_t Hs, const void* dy, const void* x, const float* mean,
+                            const float* rstd, const void* gamma, float* sums, hipStream_t s);
+hipError_t ln_dist_bwd_apply(int dtype, int64_t M, int64_t Hs, int64_t H, const void* dy, const void* x,
+                             const float* mean, const float* rstd, const void* gamma, const float* totals,
+                             const void* dx_add, void* dx, void* dgamma, void* dbeta, float* partials,
+                             hipStream_t s);
+size_t ln_dist_scratch_bytes(int64_t M, int64_t Hs);
+hipError_t slice_epilogue_fwd(int dtype, bool gelu, int64_t M, int64_t N, const void* in, const void* bias,
+                              const void* resid, void* u, void* out, hipStream_t s);
+hipError_t gelu_bwd(int dtype, int64_t M, int64_t N, const void* dg, const void* u, void* du, hipStream_t s);
+
 // bf16 MFMA kernels for gfx950.
 bool gemm_bf16_supported(const GemmArgs& a);
 size_t gemm_bf16_workspace_bytes(int64_t M, int64_t N, int64_t K);

@@ -93,10 +93,11 @@ __global__ __launch_bounds__(LN_THREADS) void ln_bwd_rowstat_kernel(int64_t M, i
                                                                     const float* __restrict__ mean,
                                                                     const float* __restrict__ rstd,
                                                                     const T* __restrict__ gamma,
+                                                                    float out_scale,
                                                                     float* __restrict__ c12) {
     __shared__ float red[4];
     const int t = threadIdx.x;
-    const float inv_h = 1.0f / (float)H;
+    const float inv_h = out_scale;   // 1/H: row means (replicated); 1: plain sums (distributed, summed over ranks later)
     for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
         const float mu = mean[row], rs = rstd[row];
         float s1 = 0.0f, s2 = 0.0f;
@@ -133,6 +134,8 @@ __global__ __launch_bounds__(LN_THREADS) void ln_bwd_tile_kernel(int64_t M, int6
                                                                  const float* __restrict__ rstd,
                                                                  const T* __restrict__ gamma,
                                                                  const float* __restrict__ c12,
+                                                                 float c_scale,
+                                                                 const T* __restrict__ add,
                                                                  T* __restrict__ dz,
                                                                  float* __restrict__ partials) {
     __shared__ float red[2][4][64][8];
@@ -144,7 +147,7 @@ __global__ __launch_bounds__(LN_THREADS) void ln_bwd_tile_kernel(int64_t M, int6
         float gm[8];
         load8(gamma + col, gm);
         for (int64_t row = m0 + rl; row < m1; row += 4) {
-            const float mu = mean[row], rs = rstd[row], c1 = c12[2 * row], c2 = c12[2 * row + 1];
+            const float mu = mean[row], rs = rstd[row], c1 = c12[2 * row] * c_scale, c2 = c12[2 * row + 1] * c_scale;
             float g[8], zz[8];
             load8(dy + row * H + col, g);
             load8(z + row * H + col, zz);
@@ -154,6 +157,12 @@ __global__ __launch_bounds__(LN_THREADS) void ln_bwd_tile_kernel(int64_t M, int6
                 dbet[e] += g[e];
                 dgam[e] = fmaf(g[e], zh, dgam[e]);
                 g[e] = (g[e] * gm[e] - c1 - zh * c2) * rs;
+            }
+            if (add) {                               // gradient arriving over the residual branch
+                float r[8];
+                load8(add + row * H + col, r);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) g[e] += r[e];
             }
             store8(dz + row * H + col, g);
         }
@@ -194,11 +203,11 @@ static hipError_t bwd_t(const LnArgs& a) {
     float* part = a.partials + 2 * a.M;
     const unsigned grid = (unsigned)(a.M < 65535 * 16 ? a.M : 65535 * 16);
     hipLaunchKernelGGL((ln_bwd_rowstat_kernel<T, MAXC>), dim3(grid), dim3(LN_THREADS), 0, a.stream, a.M, a.H,
-                       (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma, c12);
+                       (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma, 1.0f / (float)a.H, c12);
     const int64_t slabs = ln_partial_rows(a.M);
     hipLaunchKernelGGL((ln_bwd_tile_kernel<T>), dim3((unsigned)((a.H + 511) / 512), (unsigned)slabs),
                        dim3(LN_THREADS), 0, a.stream, a.M, a.H, (const T*)a.dy, (const T*)a.z, a.mean, a.rstd,
-                       (const T*)a.gamma, c12, (T*)a.dz, part);
+                       (const T*)a.gamma, c12, 1.0f, (const T*)nullptr, (T*)a.dz, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // partial rows are [slab][2][H]: gamma and beta gradients are separate buffers, so two strided sums
@@ -213,6 +222,232 @@ static hipError_t dispatch(const LnArgs& a, bool bwd) {
     if (chunks <= 2) return bwd ? bwd_t<T, 2>(a) : fwd_t<T, 2>(a);
     if (chunks <= 4) return bwd ? bwd_t<T, 4>(a) : fwd_t<T, 4>(a);
     return bwd ? bwd_t<T, 8>(a) : fwd_t<T, 8>(a);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Distributed layer normalisation (memory-optimised distribution, App. F.2 of the paper): a rank holds
+// the channel slice [M, Hs] of the activation.  Forward: per-token moments (sum x, sum x^2) of the
+// slice; after the caller's all-reduce over ranks, `ln_dist_stats` turns the totals into mean and
+// 1/sqrt(var + eps), and `ln_dist_apply` normalises the slice element-wise with them.  Backward: the
+// per-token sums (sum dy*gamma, sum dy*gamma*xhat) of the slice, all-reduced by the caller, then dx,
+// dgamma, dbeta of the slice.  The backward runs the two kernels above with x in place of the saved
+// z, plain sums out of the row pass and the totals scaled by 1/H going into the tile pass.
+// ------------------------------------------------------------------------------------------------
+template <typename T, int MAXC>
+__global__ __launch_bounds__(LN_THREADS) void ln_moments_kernel(int64_t M, int64_t Hs, const T* __restrict__ x,
+                                                                float* __restrict__ sums) {
+    __shared__ float red[4];
+    const int t = threadIdx.x;
+    for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+        float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < MAXC; ++i) {
+            const int64_t col = ((int64_t)t + LN_THREADS * i) * 8;
+            if (col < Hs) {
+                float v[8];
+                load8(x + row * Hs + col, v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { s1 += v[e]; s2 = fmaf(v[e], v[e], s2); }
+            }
+        }
+        const float a = block_sum(s1, red), b = block_sum(s2, red);
+        if (t == 0) { sums[2 * row] = a; sums[2 * row + 1] = b; }
+    }
+}
+
+__global__ void ln_stats_kernel(int64_t M, float inv_h, float eps, const float* __restrict__ totals,
+                                float* __restrict__ mean, float* __restrict__ rstd) {
+    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (row < M) {
+        const float mu = totals[2 * row] * inv_h;
+        const float var = fmaf(-mu, mu, totals[2 * row + 1] * inv_h);
+        mean[row] = mu;
+        rstd[row] = 1.0f / sqrtf(fmaxf(var, 0.0f) + eps);
+    }
+}
+
+// LN_SLAB rows x 512 columns per workgroup, as the backward tile pass.
+template <typename T>
+__global__ __launch_bounds__(LN_THREADS) void ln_apply_kernel(int64_t M, int64_t Hs, const T* __restrict__ x,
+                                                              const float* __restrict__ mean,
+                                                              const float* __restrict__ rstd,
+                                                              const T* __restrict__ gamma,
+                                                              const T* __restrict__ beta, T* __restrict__ y) {
+    const int cg = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const int64_t col = ((int64_t)blockIdx.x * 64 + cg) * 8;
+    const int64_t m0 = (int64_t)blockIdx.y * LN_SLAB, m1 = m0 + LN_SLAB < M ? m0 + LN_SLAB : M;
+    if (col >= Hs) return;
+    float gm[8], bt[8];
+    load8(gamma + col, gm);
+    load8(beta + col, bt);
+    for (int64_t row = m0 + rl; row < m1; row += 4) {
+        const float mu = mean[row], rs = rstd[row];
+        float v[8];
+        load8(x + row * Hs + col, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = fmaf((v[e] - mu) * rs, gm[e], bt[e]);
+        store8(y + row * Hs + col, v);
+    }
+}
+
+template <typename T, int MAXC>
+static hipError_t moments_t(int64_t M, int64_t Hs, const void* x, float* sums, hipStream_t s) {
+    const unsigned grid = (unsigned)(M < 65535 * 16 ? M : 65535 * 16);
+    hipLaunchKernelGGL((ln_moments_kernel<T, MAXC>), dim3(grid), dim3(LN_THREADS), 0, s, M, Hs, (const T*)x, sums);
+    return hipGetLastError();
+}
+template <typename T, int MAXC>
+static hipError_t bwd_sums_t(int64_t M, int64_t Hs, const void* dy, const void* x, const float* mean,
+                             const float* rstd, const void* gamma, float* sums, hipStream_t s) {
+    const unsigned grid = (unsigned)(M < 65535 * 16 ? M : 65535 * 16);
+    hipLaunchKernelGGL((ln_bwd_rowstat_kernel<T, MAXC>), dim3(grid), dim3(LN_THREADS), 0, s, M, Hs, (const T*)dy,
+                       (const T*)x, mean, rstd, (const T*)gamma, 1.0f, sums);
+    return hipGetLastError();
+}
+#define TPL_LN_CHUNKS(Hs, CALL2, CALL4, CALL8)                                   \
+    do {                                                                         \
+        const int64_t chunks_ = ((Hs) / 8 + LN_THREADS - 1) / LN_THREADS;        \
+        if (chunks_ <= 2) return CALL2;                                          \
+        if (chunks_ <= 4) return CALL4;                                          \
+        return CALL8;                                                            \
+    } while (0)
+
+hipError_t ln_dist_moments(int dtype, int64_t M, int64_t Hs, const void* x, float* sums, hipStream_t s) {
+    if (dtype == F32) TPL_LN_CHUNKS(Hs, (moments_t<float, 2>(M, Hs, x, sums, s)), (moments_t<float, 4>(M, Hs, x, sums, s)),
+                                    (moments_t<float, 8>(M, Hs, x, sums, s)));
+    TPL_LN_CHUNKS(Hs, (moments_t<bf16_t, 2>(M, Hs, x, sums, s)), (moments_t<bf16_t, 4>(M, Hs, x, sums, s)),
+                  (moments_t<bf16_t, 8>(M, Hs, x, sums, s)));
+}
+
+hipError_t ln_dist_stats(int64_t M, int64_t H, float eps, const float* totals, float* mean, float* rstd,
+                         hipStream_t s) {
+    hipLaunchKernelGGL(ln_stats_kernel, dim3((unsigned)((M + 255) / 256)), dim3(256), 0, s, M, 1.0f / (float)H, eps,
+                       totals, mean, rstd);
+    return hipGetLastError();
+}
+
+hipError_t ln_dist_apply(int dtype, int64_t M, int64_t Hs, const void* x, const float* mean, const float* rstd,
+                         const void* gamma, const void* beta, void* y, hipStream_t s) {
+    const dim3 grid((unsigned)((Hs + 511) / 512), (unsigned)ln_partial_rows(M));
+    if (dtype == F32)
+        hipLaunchKernelGGL((ln_apply_kernel<float>), grid, dim3(LN_THREADS), 0, s, M, Hs, (const float*)x, mean, rstd,
+                           (const float*)gamma, (const float*)beta, (float*)y);
+    else
+        hipLaunchKernelGGL((ln_apply_kernel<bf16_t>), grid, dim3(LN_THREADS), 0, s, M, Hs, (const bf16_t*)x, mean,
+                           rstd, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y);
+    return hipGetLastError();
+}
+
+hipError_t ln_dist_bwd_sums(int dtype, int64_t M, int64_t Hs, const void* dy, const void* x, const float* mean,
+                            const float* rstd, const void* gamma, float* sums, hipStream_t s) {
+    if (dtype == F32)
+        TPL_LN_CHUNKS(Hs, (bwd_sums_t<float, 2>(M, Hs, dy, x, mean, rstd, gamma, sums, s)),
+                      (bwd_sums_t<float, 4>(M, Hs, dy, x, mean, rstd, gamma, sums, s)),
+                      (bwd_sums_t<float, 8>(M, Hs, dy, x, mean, rstd, gamma, sums, s)));
+    TPL_LN_CHUNKS(Hs, (bwd_sums_t<bf16_t, 2>(M, Hs, dy, x, mean, rstd, gamma, sums, s)),
+                  (bwd_sums_t<bf16_t, 4>(M, Hs, dy, x, mean, rstd, gamma, sums, s)),
+                  (bwd_sums_t<bf16_t, 8>(M, Hs, dy, x, mean, rstd, gamma, sums, s)));
+}
+
+// partials: ln_partial_rows(M) * 2 * Hs floats.
+hipError_t ln_dist_bwd_apply(int dtype, int64_t M, int64_t Hs, int64_t H, const void* dy, const void* x,
+                             const float* mean, const float* rstd, const void* gamma, const float* totals,
+                             const void* dx_add, void* dx, void* dgamma, void* dbeta, float* partials,
+                             hipStream_t s) {
+    const int64_t slabs = ln_partial_rows(M);
+    const dim3 grid((unsigned)((Hs + 511) / 512), (unsigned)slabs);
+    const float c_scale = 1.0f / (float)H;
+    if (dtype == F32)
+        hipLaunchKernelGGL((ln_bwd_tile_kernel<float>), grid, dim3(LN_THREADS), 0, s, M, Hs, (const float*)dy,
+                           (const float*)x, mean, rstd, (const float*)gamma, totals, c_scale, (const float*)dx_add,
+                           (float*)dx, partials);
+    else
+        hipLaunchKernelGGL((ln_bwd_tile_kernel<bf16_t>), grid, dim3(LN_THREADS), 0, s, M, Hs, (const bf16_t*)dy,
+                           (const bf16_t*)x, mean, rstd, (const bf16_t*)gamma, totals, c_scale, (const bf16_t*)dx_add,
+                           (bf16_t*)dx, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = sum_partials_strided(dtype, slabs, Hs, partials, 2 * Hs, dgamma, s);
+    if (e != hipSuccess) return e;
+    return sum_partials_strided(dtype, slabs, Hs, partials + Hs, 2 * Hs, dbeta, s);
+}
+size_t ln_dist_scratch_bytes(int64_t M, int64_t Hs) { return (size_t)ln_partial_rows(M) * 2 * Hs * sizeof(float); }
+
+// ------------------------------------------------------------------------------------------------
+// What a rank does to the slice [M, N] it keeps after a reduce-scatter (the product of an input-split
+// linear is a partial sum, so bias, residual and activation cannot ride in the GEMM epilogue):
+// v = in + bias (+ resid); with GeLU u = v is kept and out = gelu(v), otherwise out = v.
+// Backward with GeLU: din = dout * gelu'(u).
+// ------------------------------------------------------------------------------------------------
+template <typename T, bool GELU>
+__global__ __launch_bounds__(256) void slice_epilogue_fwd_kernel(int64_t M, int64_t N, const T* __restrict__ in,
+                                                                 const T* __restrict__ bias,
+                                                                 const T* __restrict__ resid, T* __restrict__ u,
+                                                                 T* __restrict__ out) {
+    const int64_t chunks = N / 8, total = M * chunks;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t col = (i % chunks) * 8, off = (i / chunks) * N + col;
+        float v[8], b[8];
+        load8(in + off, v);
+        load8(bias + col, b);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += b[e];
+        if (resid) {
+            load8(resid + off, b);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += b[e];
+        }
+        if (GELU) {
+            store8(u + off, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+        }
+        store8(out + off, v);
+    }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(int64_t total8, const T* __restrict__ dg,
+                                                       const T* __restrict__ u, T* __restrict__ du) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total8; i += (int64_t)gridDim.x * 256) {
+        float v[8], w[8];
+        load8(dg + i * 8, v);
+        load8(u + i * 8, w);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(w[e]);
+        store8(du + i * 8, v);
+    }
+}
+static unsigned ew_grid(int64_t items) {
+    int64_t b = (items + 255) / 256;
+    return (unsigned)(b < 1 ? 1 : (b > 256 * 32 ? 256 * 32 : b));
+}
+template <typename T>
+static hipError_t slice_fwd_t(bool gelu, int64_t M, int64_t N, const void* in, const void* bias, const void* resid,
+                              void* u, void* out, hipStream_t s) {
+    const unsigned grid = ew_grid(M * (N / 8));
+    if (gelu)
+        hipLaunchKernelGGL((slice_epilogue_fwd_kernel<T, true>), dim3(grid), dim3(256), 0, s, M, N, (const T*)in,
+                           (const T*)bias, (const T*)resid, (T*)u, (T*)out);
+    else
+        hipLaunchKernelGGL((slice_epilogue_fwd_kernel<T, false>), dim3(grid), dim3(256), 0, s, M, N, (const T*)in,
+                           (const T*)bias, (const T*)resid, (T*)u, (T*)out);
+    return hipGetLastError();
+}
+hipError_t slice_epilogue_fwd(int dtype, bool gelu, int64_t M, int64_t N, const void* in, const void* bias,
+                              const void* resid, void* u, void* out, hipStream_t s) {
+    return dtype == F32 ? slice_fwd_t<float>(gelu, M, N, in, bias, resid, u, out, s)
+                        : slice_fwd_t<bf16_t>(gelu, M, N, in, bias, resid, u, out, s);
+}
+hipError_t gelu_bwd(int dtype, int64_t M, int64_t N, const void* dg, const void* u, void* du, hipStream_t s) {
+    const int64_t total8 = M * N / 8;
+    const unsigned grid = ew_grid(total8);
+    if (dtype == F32)
+        hipLaunchKernelGGL((gelu_bwd_kernel<float>), dim3(grid), dim3(256), 0, s, total8, (const float*)dg,
+                           (const float*)u, (float*)du);
+    else
+        hipLaunchKernelGGL((gelu_bwd_kernel<bf16_t>), dim3(grid), dim3(256), 0, s, total8, (const bf16_t*)dg,
+                           (const bf16_t*)u, (bf16_t*)du);
+    return hipGetLastError();
 }
 
 hipError_t ln_fwd(const LnArgs& a) { return a.dtype == F32 ? dispatch<float>(a, false) : dispatch<bf16_t>(a, false); }

@@ -366,6 +366,113 @@ int tp_layer_ln_bwd(int dtype, int64_t M, int64_t H, const void* dy, const void*
     return ln_bwd(l) == hipSuccess ? TPL_OK : TPL_EHIP;
 }
 
+static int dist_check(int dtype, int64_t M, int64_t Hs) {
+    if (dtype != TPL_F32 && dtype != TPL_BF16) return TPL_EINVAL;
+    if (M <= 0 || Hs <= 0) return TPL_EINVAL;
+    if (!ln_supported(Hs)) return TPL_EUNSUPPORTED;
+    return TPL_OK;
+}
+static int hip_rc(hipError_t e) { return e == hipSuccess ? TPL_OK : TPL_EHIP; }
+
+int tp_layer_ln_moments(int dtype, int64_t M, int64_t Hs, const void* x_loc, float* sums, void* hip_stream) {
+    int rc = dist_check(dtype, M, Hs);
+    if (rc) return rc;
+    if (!x_loc || !sums) return TPL_EINVAL;
+    if (misaligned(x_loc) || misaligned(sums)) return TPL_EALIGN;
+    return hip_rc(ln_dist_moments(dtype, M, Hs, x_loc, sums, (hipStream_t)hip_stream));
+}
+
+int tp_layer_ln_stats(int64_t M, int64_t H, float eps, const float* totals, float* mean, float* rstd,
+                      void* hip_stream) {
+    if (M <= 0 || H <= 0 || !(eps >= 0.0f) || !totals || !mean || !rstd) return TPL_EINVAL;
+    return hip_rc(ln_dist_stats(M, H, eps, totals, mean, rstd, (hipStream_t)hip_stream));
+}
+
+int tp_layer_ln_apply_fwd(int dtype, int64_t M, int64_t Hs, const void* x_loc, const float* mean,
+                          const float* rstd, const void* gamma_loc, const void* beta_loc, void* y,
+                          void* hip_stream) {
+    int rc = dist_check(dtype, M, Hs);
+    if (rc) return rc;
+    if (!x_loc || !mean || !rstd || !gamma_loc || !beta_loc || !y) return TPL_EINVAL;
+    const void* ptrs[] = {x_loc, gamma_loc, beta_loc, y};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    return hip_rc(ln_dist_apply(dtype, M, Hs, x_loc, mean, rstd, gamma_loc, beta_loc, y, (hipStream_t)hip_stream));
+}
+
+int tp_layer_ln_apply_bwd_sums(int dtype, int64_t M, int64_t Hs, const void* dy, const void* x_loc,
+                               const float* mean, const float* rstd, const void* gamma_loc, float* sums,
+                               void* hip_stream) {
+    int rc = dist_check(dtype, M, Hs);
+    if (rc) return rc;
+    if (!dy || !x_loc || !mean || !rstd || !gamma_loc || !sums) return TPL_EINVAL;
+    const void* ptrs[] = {dy, x_loc, gamma_loc};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    return hip_rc(ln_dist_bwd_sums(dtype, M, Hs, dy, x_loc, mean, rstd, gamma_loc, sums, (hipStream_t)hip_stream));
+}
+
+size_t tp_layer_ln_apply_workspace_bytes(int64_t M, int64_t Hs) {
+    if (M <= 0 || Hs <= 0) return 0;
+    return up(ln_dist_scratch_bytes(M, Hs));
+}
+
+int tp_layer_ln_apply_bwd(int dtype, int64_t M, int64_t Hs, int64_t H, const void* dy, const void* x_loc,
+                          const float* mean, const float* rstd, const void* gamma_loc, const float* totals,
+                          const void* dx_add, void* dx, void* dgamma_loc, void* dbeta_loc, void* ws,
+                          size_t ws_bytes, void* hip_stream) {
+    int rc = dist_check(dtype, M, Hs);
+    if (rc) return rc;
+    if (H < Hs) return TPL_EINVAL;
+    if (!dy || !x_loc || !mean || !rstd || !gamma_loc || !totals || !dx || !dgamma_loc || !dbeta_loc || !ws)
+        return TPL_EINVAL;
+    const void* ptrs[] = {dy, x_loc, gamma_loc, dx_add, dx, dgamma_loc, dbeta_loc, ws};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    if (ws_bytes < tp_layer_ln_apply_workspace_bytes(M, Hs)) return TPL_EWORKSPACE;
+    return hip_rc(ln_dist_bwd_apply(dtype, M, Hs, H, dy, x_loc, mean, rstd, gamma_loc, totals, dx_add, dx,
+                                    dgamma_loc, dbeta_loc, (float*)ws, (hipStream_t)hip_stream));
+}
+
+static int ew_check(int dtype, int64_t M, int64_t N) {
+    if (dtype != TPL_F32 && dtype != TPL_BF16) return TPL_EINVAL;
+    if (M <= 0 || N <= 0) return TPL_EINVAL;
+    if (N % 8) return TPL_EUNSUPPORTED;
+    return TPL_OK;
+}
+
+int tp_layer_slice_epilogue_fwd(int dtype, int act, int64_t M, int64_t N, const void* in, const void* bias,
+                                const void* resid, void* u, void* out, void* hip_stream) {
+    int rc = ew_check(dtype, M, N);
+    if (rc) return rc;
+    if (act != TPL_ACT_NONE && act != TPL_ACT_GELU) return TPL_EINVAL;
+    if (!in || !bias || !out || (act == TPL_ACT_GELU && !u)) return TPL_EINVAL;
+    const void* ptrs[] = {in, bias, resid, u, out};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    return hip_rc(slice_epilogue_fwd(dtype, act == TPL_ACT_GELU, M, N, in, bias, resid, u, out,
+                                     (hipStream_t)hip_stream));
+}
+
+size_t tp_layer_slice_epilogue_workspace_bytes(int64_t M, int64_t N) {
+    if (M <= 0 || N <= 0) return 0;
+    return up(colsum_scratch_bytes(M, N));
+}
+
+int tp_layer_slice_epilogue_bwd(int dtype, int act, int64_t M, int64_t N, const void* dout, const void* u,
+                                void* din, void* dbias, void* ws, size_t ws_bytes, void* hip_stream) {
+    int rc = ew_check(dtype, M, N);
+    if (rc) return rc;
+    if (act != TPL_ACT_NONE && act != TPL_ACT_GELU) return TPL_EINVAL;
+    if (!dout || !dbias || !ws || (act == TPL_ACT_GELU && (!u || !din))) return TPL_EINVAL;
+    const void* ptrs[] = {dout, u, din, dbias, ws};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    if (ws_bytes < tp_layer_slice_epilogue_workspace_bytes(M, N)) return TPL_EWORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const void* d = dout;
+    if (act == TPL_ACT_GELU) {
+        if (gelu_bwd(dtype, M, N, dout, u, din, s) != hipSuccess) return TPL_EHIP;
+        d = din;
+    }
+    return hip_rc(colsum(dtype, M, N, d, dbias, (float*)ws, s));
+}
+
 size_t tp_layer_gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
     return std::max(gemm_ws(dtype, M, N, K), ALIGN);
