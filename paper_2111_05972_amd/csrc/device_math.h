@@ -9,15 +9,29 @@ typedef __bf16 bf16_t;
 template <typename T> __device__ __forceinline__ float to_f32(T v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f32(float v) { return (T)v; }
 
-// gelu(u) = u * Phi(u) with the erf form of the normal CDF.
-__device__ __forceinline__ float gelu_f(float u) {
-    return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f));
+// The exact (erf) GeLU: gelu(u) = u * Phi(u), Phi the normal CDF, Phi(u) = 0.5 * (1 + erf(u / sqrt 2)).
+// Phi is evaluated through the lower tail, Phi(-|u|) = 0.5 * erfc(|u| / sqrt 2), with the rational
+// approximation erfc(x) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-x^2), t = 1 / (1 + p x)
+// (Abramowitz & Stegun 7.1.26, absolute error below 1.5e-7, i.e. float rounding level for values in [0, 1]);
+// no cancellation for negative u, one exp and one reciprocal per element, and the same exp(-u^2 / 2)
+// serves the density in the derivative.  About a third of the instructions of the library erff.
+struct PhiParts { float Phi, e; };   // Phi(u) and exp(-u^2 / 2)
+__device__ __forceinline__ PhiParts normal_cdf(float u) {
+    const float x = fabsf(u) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    const float e = __expf(-x * x);
+    float q = fmaf(1.061405429f, t, -1.453152027f);
+    q = fmaf(q, t, 1.421413741f);
+    q = fmaf(q, t, -0.284496736f);
+    q = fmaf(q, t, 0.254829592f);
+    q = 0.5f * q * t * e;
+    return PhiParts{u < 0.0f ? q : 1.0f - q, e};
 }
-// d/du gelu(u) = Phi(u) + u * phi(u)
+__device__ __forceinline__ float gelu_f(float u) { return u * normal_cdf(u).Phi; }
+// d/du gelu(u) = Phi(u) + u * phi(u), phi the normal density
 __device__ __forceinline__ float gelu_grad_f(float u) {
-    float Phi = 0.5f * (1.0f + erff(u * 0.70710678118654752440f));
-    float phi = 0.39894228040143267794f * __expf(-0.5f * u * u);
-    return Phi + u * phi;
+    const PhiParts c = normal_cdf(u);
+    return fmaf(u * 0.39894228040143267794f, c.e, c.Phi);
 }
 
 // Eight consecutive elements <-> eight floats with 16-byte accesses (pointer 16-byte aligned).

@@ -36,6 +36,7 @@
 #include <hip/hip_runtime.h>
 #include <type_traits>
 
+#include <algorithm>
 #include <cstdlib>
 
 #include "device_math.h"
@@ -74,8 +75,26 @@ struct GemmParams {
     int M, N, K;
     int lda, ldb;          // row strides (elements) of A and B as stored
     int epi;
-    int tiles_m, tiles_n, nk;
+    int tiles_m, tiles_n;
+    int nk;                // k-steps of one workgroup (one K share when K is split)
+    int nk_total;          // k-steps of the whole K
+    float* partial;        // K split over several workgroups: float partial sums [share][M][N], else null
 };
+
+// Which K share a workgroup computes.  The workgroup list is share-major (all tiles of share 0, then all
+// tiles of share 1, ...), so the tiles in flight together on an XCD walk the same k range and share panels.
+struct KShare { int tile, kt0, nk, kend; float* partial; };
+__device__ __forceinline__ KShare k_share(const GemmParams& p, int list_pos) {
+    KShare s;
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int share = list_pos / ntiles;
+    s.tile = list_pos - share * ntiles;
+    s.kt0 = share * p.nk;
+    s.nk = p.nk_total - s.kt0 < p.nk ? p.nk_total - s.kt0 : p.nk;
+    s.kend = (s.kt0 + s.nk) * DK < p.K ? (s.kt0 + s.nk) * DK : p.K;
+    s.partial = p.partial ? p.partial + (int64_t)share * p.M * p.N : nullptr;
+    return s;
+}
 
 // ---- LDS layouts -------------------------------------------------------------------------------
 // K-major stage tile: 64-byte rows (32 k), four 16-byte chunks, swizzled by row.
@@ -223,7 +242,7 @@ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, 
 // Epilogue of one wavefront: accumulators -> its LDS staging area -> 16-byte row accesses.
 template <typename TL>
 __device__ __forceinline__ void epilogue(const GemmParams& p, const f32x16 (&acc)[TL::TM][TL::TN], char* smem,
-                                         int wave, int lane, int m0, int n0) {
+                                         int wave, int lane, int m0, int n0, float* partial) {
     constexpr int TM = TL::TM, TN = TL::TN;
     const int wm = wave >> 1, wn = wave & 1;
     constexpr int LPR = TN * 4;               // lanes per staged row (8 columns each)
@@ -233,7 +252,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const f32x16 (&acc
     const int er = lane / LPR, ec = (lane % LPR) * 8;
     const int gn = n0 + wn * TN * 32 + ec;
     float bias8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (p.bias && gn < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + gn), bias8);
+    if (p.bias && !partial && gn < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + gn), bias8);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         // accumulator register v of block (i,j): row (v/4)*8 + (lane/32)*4 + v%4, column j*32 + lane%32
@@ -253,6 +272,11 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const f32x16 (&acc
                 float4 x0 = src[0], x1 = src[1];
                 float v8[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
                 const int64_t idx = (int64_t)gm * p.N + gn;
+                if (partial) {                     // one K share: the raw float sums; the epilogue is applied
+                    float4* dst = reinterpret_cast<float4*>(partial + idx);   // when the shares are summed
+                    dst[0] = x0; dst[1] = x1;
+                    continue;
+                }
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v8[e] += bias8[e];
                 if (p.resid) {
@@ -284,7 +308,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const int tile = share_of_block(blockIdx.x, gridDim.x);
+    const KShare sh = k_share(p, share_of_block(blockIdx.x, gridDim.x));
 
     const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)(A_KMAJ ? p.M : p.K) * p.lda * 2));
     const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
@@ -292,7 +316,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     constexpr int NM = TM * TN;                                   // matrix instructions per half stage
 
     int tm, tn;
-    tile_coords(tile, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     f32x16 acc[TM][TN];
@@ -309,7 +333,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     dma_offsets<A_KMAJ, TM>(offa, oka, kca, p.lda, m0, p.M, wave, lane);
     dma_offsets<B_KMAJ, TN>(offb, okb, kcb, p.ldb, n0, p.N, wave, lane);
 
-    // Ring slot of stage s is s % STAGES.  Stages past the end of K are issued too (all chunks out of
+    // Ring slot of stage s (counted from the start of this workgroup's K share) is s % STAGES.  Stages past
+    // the end of the share are issued too (all chunks out of
     // bounds: zero fill, no memory traffic) so the number of loads in flight never changes.  The loads
     // of a stage are numbered 0..LOADS-1 (A chunks, then B chunks); every piece of the loop body below
     // is fenced so that the instruction order is the one written: one fragment read or one direct
@@ -318,14 +343,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     constexpr int L = TL::LOADS, L1 = L / 2;                     // part 1: loads [0,L1), part 2: [L1,L)
     auto dma_one = [&](int s, int d) {
         const unsigned buf = lds0 + (s % DSTAGES) * TL::STAGE_BYTES;
-        const int k0 = s * DK;
+        const int k0 = (sh.kt0 + s) * DK;
         if (d < TM) {
-            bool ok = A_KMAJ ? (k0 + kca < p.K) : (oka[d] && k0 < p.K);
+            bool ok = A_KMAJ ? (k0 + kca < sh.kend) : (oka[d] && k0 < sh.kend);
             unsigned step = A_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.lda * 2);
             buffer_load_lds_b128(ra, buf + (wave_u * TM + d) * 1024, ok ? offa[d] + step : OOB_OFFSET);
         } else {
             const int e = d - TM;
-            bool ok = B_KMAJ ? (k0 + kcb < p.K) : (okb[e] && k0 < p.K);
+            bool ok = B_KMAJ ? (k0 + kcb < sh.kend) : (okb[e] && k0 < sh.kend);
             unsigned step = B_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.ldb * 2);
             buffer_load_lds_b128(rb, buf + TL::A_BYTES + (wave_u * TN + e) * 1024, ok ? offb[e] + step : OOB_OFFSET);
         }
@@ -373,7 +398,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     for (int r = 0; r < TM + TN; ++r) read_one(fa0, fb0, 0, 0, r);
     __builtin_amdgcn_sched_barrier(0);
 
-    for (int kt = 0; kt < p.nk; ++kt) {
+    for (int kt = 0; kt < sh.nk; ++kt) {
         // first half: math on k-substep 0, fragments of substep 1 are read, rest of stage kt+STAGES-1 is fetched
         half(fa0, fb0, fa1, fb1, kt, 1, kt + DSTAGES - 1, ICL1{}, ICL{});
         // stage kt+1 has landed for this wavefront once only the newer stages are in flight; after the
@@ -387,7 +412,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     wait_vmcnt<0>();                                             // drain the ring before LDS is reused
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
-    epilogue<TL>(p, acc, smem, wave, lane, m0, n0);
+    epilogue<TL>(p, acc, smem, wave, lane, m0, n0, sh.partial);
 }
 
 // =================================================================================================
@@ -437,9 +462,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
     constexpr int A_BYTES = ST::template a_bytes<A_KMAJ>();
     constexpr int LPS = TM + TN;                                  // loads per k-step and fetching wavefront
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int tile = share_of_block(blockIdx.x, gridDim.x);
+    const KShare sh = k_share(p, share_of_block(blockIdx.x, gridDim.x));   // sh.kt0 is even (host)
     int tm, tn;
-    tile_coords(tile, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     if (wave >= 4) {
@@ -468,32 +493,34 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
         } else {
             dma_offsets<A_KMAJ, TM>(offa, oka, kca, p.lda, m0, p.M, w, lane);
         }
+        // k-steps kt and wide units u below count from the start of this workgroup's K share
         auto load_b = [&](int kt) {                               // k-step kt of B into its slot
             const unsigned buf = lds_b + (kt % NB) * ST::B_SLOT;
-            const int k0 = kt * DK;
+            const int k0 = (sh.kt0 + kt) * DK;
             const unsigned step = B_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.ldb * 2);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                bool ok = B_KMAJ ? (k0 + kcb < p.K) : (okb[j] && k0 < p.K);
+                bool ok = B_KMAJ ? (k0 + kcb < sh.kend) : (okb[j] && k0 < sh.kend);
                 buffer_load_lds_b128(rb, buf + (w * TN + j) * 1024, ok ? offb[j] + step : OOB_OFFSET);
             }
         };
         auto load_a32 = [&](int kt) {
             const unsigned buf = lds_a + (kt % NB) * ST::A_SLOT32;
-            const int k0 = kt * DK;
+            const int k0 = (sh.kt0 + kt) * DK;
             const unsigned step = A_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.lda * 2);
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
-                bool ok = A_KMAJ ? (k0 + kca < p.K) : (oka[j] && k0 < p.K);
+                bool ok = A_KMAJ ? (k0 + kca < sh.kend) : (oka[j] && k0 < sh.kend);
                 buffer_load_lds_b128(ra, buf + (w * TM + j) * 1024, ok ? offa[j] + step : OOB_OFFSET);
             }
         };
         auto load_a64 = [&](int u, int half) {                    // half 0/1 of unit u (k = 64 u ..)
             const unsigned buf = lds_a + (u % NAW) * ST::A_SLOT64;
+            const int ua = (sh.kt0 >> 1) + u;
 #pragma unroll
             for (int q = half * TM; q < (half + 1) * TM; ++q)
                 buffer_load_lds_b128(ra, buf + (w * 2 * TM + q) * 1024,
-                                     64 * u + kcw[q] < p.K ? offw[q] + (unsigned)u * 128u : OOB_OFFSET);
+                                     64 * ua + kcw[q] < sh.kend ? offw[q] + (unsigned)ua * 128u : OOB_OFFSET);
         };
         // prologue: everything the rings hold, except the second half of the last wide unit
         if (WIDE) {
@@ -515,7 +542,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
         constexpr int W_B = (NB - 2) * LPS;
         constexpr int W_A = WIDE ? TN + 2 * LPS : TN + (NB - 2) * LPS;
         constexpr int W = W_A < W_B ? W_A : W_B;
-        for (int kt = 0; kt < p.nk; ++kt) {
+        for (int kt = 0; kt < sh.nk; ++kt) {
             // The first two k-steps of a wide A come straight after the prologue, which ends with the
             // B steps: fewer loads follow the ones needed than in the steady state.
             if (WIDE && kt == 0) wait_vmcnt<(NB - 2) * TN>();                  // B step 1
@@ -585,7 +612,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) rd_b(fb[0][j], 0, 0, j);
     __builtin_amdgcn_sched_barrier(0);
-    for (int kt = 0; kt < p.nk; ++kt) {
+    for (int kt = 0; kt < sh.nk; ++kt) {
         mhalf(C0{}, kt, 1);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
@@ -594,7 +621,45 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
-    epilogue<ST>(p, acc, smem, wave, lane, m0, n0);
+    epilogue<ST>(p, acc, smem, wave, lane, m0, n0, sh.partial);
+}
+
+// Sum of the K shares in share order, then the epilogue; 8 columns per thread, every access 16 or 32 bytes.
+__global__ __launch_bounds__(256) void gemm_sum_shares_kernel(GemmParams p, int shares) {
+    const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = chunk * 8;
+    const int64_t mn = (int64_t)p.M * p.N;
+    if (idx >= mn) return;
+    float v8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int s = 0; s < shares; ++s) {
+        const float4* src = reinterpret_cast<const float4*>(p.partial + s * mn + idx);
+        const float4 x0 = src[0], x1 = src[1];
+        v8[0] += x0.x; v8[1] += x0.y; v8[2] += x0.z; v8[3] += x0.w;
+        v8[4] += x1.x; v8[5] += x1.y; v8[6] += x1.z; v8[7] += x1.w;
+    }
+    if (p.bias) {
+        float b8[8];
+        unpack8(*reinterpret_cast<const uint4*>(p.bias + idx % p.N), b8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v8[e] += b8[e];
+    }
+    if (p.resid) {
+        float r8[8];
+        unpack8(*reinterpret_cast<const uint4*>(p.resid + idx), r8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v8[e] += r8[e];
+    }
+    if (p.epi == EPI_GELU) {
+        *reinterpret_cast<uint4*>(p.aux + idx) = pack8(v8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v8[e] = gelu_f(v8[e]);
+    } else if (p.epi == EPI_DGELU) {
+        float u8[8];
+        unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), u8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v8[e] *= gelu_grad_f(u8[e]);
+    }
+    *reinterpret_cast<uint4*>(p.C + idx) = pack8(v8);
 }
 
 
@@ -607,10 +672,8 @@ bool gemm_bf16_supported(const GemmArgs& a) {
     return tiles < (1 << 24) && a.K < (1 << 24);
 }
 
-size_t gemm_bf16_workspace_bytes(int64_t, int64_t, int64_t) { return 0; }
-
 template <typename TL, bool AK, bool BK_>
-static hipError_t launch(GemmParams p, const GemmArgs& a) {
+static hipError_t launch(GemmParams p, const GemmArgs& a, int shares) {
     static bool attr_set = false;   // raising the dynamic LDS limit is a per-function, one-off call
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<TL, AK, BK_>),
@@ -620,22 +683,22 @@ static hipError_t launch(GemmParams p, const GemmArgs& a) {
     }
     p.tiles_m = (int)((a.M + TL::BM - 1) / TL::BM);
     p.tiles_n = (int)((a.N + TL::BN - 1) / TL::BN);
-    hipLaunchKernelGGL((gemm_bf16_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n), dim3(256),
+    hipLaunchKernelGGL((gemm_bf16_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(256),
                        TL::LDS_BYTES, a.stream, p);
     return hipGetLastError();
 }
 
 template <typename TL>
-static hipError_t launch_layout(const GemmParams& p, const GemmArgs& a) {
+static hipError_t launch_layout(const GemmParams& p, const GemmArgs& a, int shares) {
     const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
-    if (a_kmaj && b_kmaj) return launch<TL, true, true>(p, a);
-    if (a_kmaj && !b_kmaj) return launch<TL, true, false>(p, a);
-    if (!a_kmaj && b_kmaj) return launch<TL, false, true>(p, a);
-    return launch<TL, false, false>(p, a);
+    if (a_kmaj && b_kmaj) return launch<TL, true, true>(p, a, shares);
+    if (a_kmaj && !b_kmaj) return launch<TL, true, false>(p, a, shares);
+    if (!a_kmaj && b_kmaj) return launch<TL, false, true>(p, a, shares);
+    return launch<TL, false, false>(p, a, shares);
 }
 
 template <typename ST, bool AK, bool BK_>
-static hipError_t launch_spec(GemmParams p, const GemmArgs& a) {
+static hipError_t launch_spec(GemmParams p, const GemmArgs& a, int shares) {
     constexpr int LDS = ST::template lds_bytes<AK>();
     static bool attr_set = false;
     if (!attr_set) {
@@ -646,16 +709,16 @@ static hipError_t launch_spec(GemmParams p, const GemmArgs& a) {
     }
     p.tiles_m = (int)((a.M + ST::BM - 1) / ST::BM);
     p.tiles_n = (int)((a.N + ST::BN - 1) / ST::BN);
-    hipLaunchKernelGGL((gemm_bf16_spec_kernel<ST, AK, BK_>), dim3(p.tiles_m * p.tiles_n), dim3(512), LDS, a.stream, p);
+    hipLaunchKernelGGL((gemm_bf16_spec_kernel<ST, AK, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(512), LDS, a.stream, p);
     return hipGetLastError();
 }
 template <typename ST>
-static hipError_t launch_spec_layout(const GemmParams& p, const GemmArgs& a) {
+static hipError_t launch_spec_layout(const GemmParams& p, const GemmArgs& a, int shares) {
     const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
-    if (a_kmaj && b_kmaj) return launch_spec<ST, true, true>(p, a);
-    if (a_kmaj && !b_kmaj) return launch_spec<ST, true, false>(p, a);
-    if (!a_kmaj && b_kmaj) return launch_spec<ST, false, true>(p, a);
-    return launch_spec<ST, false, false>(p, a);
+    if (a_kmaj && b_kmaj) return launch_spec<ST, true, true>(p, a, shares);
+    if (a_kmaj && !b_kmaj) return launch_spec<ST, true, false>(p, a, shares);
+    if (!a_kmaj && b_kmaj) return launch_spec<ST, false, true>(p, a, shares);
+    return launch_spec<ST, false, false>(p, a, shares);
 }
 
 // Tile variants.  The host launches the one with the least estimated time
@@ -678,26 +741,55 @@ static int compute_units() {
 }
 
 constexpr int NVARIANTS = 5;
-static int pick_variant(int64_t M, int64_t N, int64_t K, bool a_kmaj) {
-    const char* e = getenv("TPL_GEMM_TILE");          // tuning / test override: one digit
-    if (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) return e[0] - '0';
+constexpr int MAX_SHARES = 16;
+struct Plan { int variant, shares, nk_share; };
+
+// Splitting K.  A GEMM with few output tiles and a long K (the data gradient of a narrow projection: N = 1536,
+// K = 12288 ... 49152) leaves compute units idle or gives each a very long serial K walk.  Its K range is then
+// cut into `shares` equal runs of k-steps, one workgroup per (tile, share); every workgroup writes its float
+// partial sums to the workspace and a second kernel adds the shares in share order and applies the epilogue,
+// so the result does not depend on scheduling.  The estimate charges that second pass with its memory traffic.
+static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj) {
     static const int bm[NVARIANTS] = {256, 256, 128, 192, 256}, bn[NVARIANTS] = {256, 192, 128, 192, 192};
     static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2, 1};
     static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658};
     static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0};
+    const char* e = getenv("TPL_GEMM_TILE");          // tuning / test overrides: one digit; a number
+    const int forced_v = (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) ? e[0] - '0' : -1;
+    const char* es = getenv("TPL_GEMM_SHARES");
+    const int forced_s = es ? atoi(es) : 0;
     const int cus = compute_units();
-    const double nk = (double)((K + DK - 1) / DK);
-    int best = 0;
-    double best_c = 0;
+    const int nk = (int)((K + DK - 1) / DK);
+    Plan best{0, 1, nk};
+    double best_c = -1;
     for (int v = 0; v < NVARIANTS; ++v) {
+        if (forced_v >= 0 && v != forced_v) continue;
         // the variant with fetch-only wavefronts is built for a K-major A (its MN-major A path spills)
-        if (v == 4 && !a_kmaj) continue;
-        int64_t tiles = ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]);
-        double per_cu = (double)((tiles + cus - 1) / cus);
-        double c = per_cu * nk * us_per_stage[v] + fixed_us[v] * (wgs_per_cu[v] == 1 ? per_cu : 1.0);
-        if (v == 0 || c < best_c) { best = v; best_c = c; }
+        if (forced_v < 0 && v == 4 && !a_kmaj) continue;
+        const int64_t tiles = ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]);
+        for (int want = 1; want <= MAX_SHARES; ++want) {
+            if (forced_s > 0 && want != (forced_s < MAX_SHARES ? forced_s : MAX_SHARES)) continue;
+            if (forced_s <= 0 && want > 1 && (tiles * (want - 1) >= cus || nk / want < 48)) break;
+            int per = (nk + want - 1) / want;
+            if (v == 4) per = (per + 1) & ~1;          // its wide A slots hold two k-steps: shares start on even steps
+            const int shares = (nk + per - 1) / per;
+            if (forced_s <= 0 && shares != want) continue;   // the same plan as a smaller `want`
+            const double per_cu = (double)((tiles * shares + cus - 1) / cus);
+            double c = per_cu * per * us_per_stage[v] + fixed_us[v] * (wgs_per_cu[v] == 1 ? per_cu : 1.0);
+            if (shares > 1) c += 6.0 + (double)M * N * (8.0 * shares + 2.0) / 3.0e6;   // second pass at ~3 TB/s
+            if (best_c < 0 || c < best_c) { best = Plan{v, shares, per}; best_c = c; }
+        }
     }
     return best;
+}
+
+size_t gemm_bf16_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    size_t need = 0;
+    for (int a_kmaj = 0; a_kmaj < 2; ++a_kmaj) {
+        const Plan pl = make_plan(M, N, K, a_kmaj != 0);
+        if (pl.shares > 1) need = std::max(need, (size_t)pl.shares * (size_t)M * (size_t)N * sizeof(float));
+    }
+    return need;
 }
 
 hipError_t gemm_bf16(const GemmArgs& a) {
@@ -709,14 +801,27 @@ hipError_t gemm_bf16(const GemmArgs& a) {
     p.ldb = a.trans_b ? (int)a.K : (int)a.N;
     p.epi = a.epi;
     p.tiles_m = p.tiles_n = 0;
-    p.nk = (int)((a.K + DK - 1) / DK);
-    switch (pick_variant(a.M, a.N, a.K, !a.trans_a)) {
-        case 4: return launch_spec_layout<SpecTile<4, 3>>(p, a);   // 256 x 192, fetch and math wavefronts
-        case 1: return launch_layout<Tile<4, 3, 4>>(p, a);    // 256 x 192
-        case 2: return launch_layout<Tile<2, 2, 4>>(p, a);    // 128 x 128, two workgroups per CU
-        case 3: return launch_layout<Tile<3, 3, 3>>(p, a);    // 192 x 192, two workgroups per CU
-        default: return launch_layout<Tile<4, 4, 4>>(p, a);   // 256 x 256
+    const Plan pl = make_plan(a.M, a.N, a.K, !a.trans_a);
+    p.nk_total = (int)((a.K + DK - 1) / DK);
+    p.nk = pl.nk_share;
+    p.partial = nullptr;
+    if (pl.shares > 1) {
+        if (a.ws == nullptr || a.ws_bytes < (size_t)pl.shares * (size_t)a.M * (size_t)a.N * sizeof(float))
+            return hipErrorInvalidValue;
+        p.partial = (float*)a.ws;
     }
+    hipError_t e;
+    switch (pl.variant) {
+        case 4: e = launch_spec_layout<SpecTile<4, 3>>(p, a, pl.shares); break;   // 256 x 192, fetch and math wavefronts
+        case 1: e = launch_layout<Tile<4, 3, 4>>(p, a, pl.shares); break;    // 256 x 192
+        case 2: e = launch_layout<Tile<2, 2, 4>>(p, a, pl.shares); break;    // 128 x 128, two workgroups per CU
+        case 3: e = launch_layout<Tile<3, 3, 3>>(p, a, pl.shares); break;    // 192 x 192, two workgroups per CU
+        default: e = launch_layout<Tile<4, 4, 4>>(p, a, pl.shares); break;   // 256 x 256
+    }
+    if (e != hipSuccess || pl.shares == 1) return e;
+    const int64_t chunks = a.M * a.N / 8;
+    hipLaunchKernelGGL(gemm_sum_shares_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, a.stream, p, pl.shares);
+    return hipGetLastError();
 }
 
 }  // namespace tpl

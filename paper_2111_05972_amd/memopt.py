@@ -58,9 +58,13 @@ class MemOptRank:
         self.dg, self.du, self.dhid = e(M, self.Il), e(M, self.Il), e(M, self.Hs)
         self.dy1, self.dx = e(M, self.Hs), e(M, self.Hs)
         self.d_o, self.dqkv, self.dsum = e(M, self.Hl), e(M, 3 * self.Hl), f(self.B, self.nl, self.S)
-        nws = max(B.tp_layer_ln_apply_workspace_bytes(M, self.Hs),
-                  B.tp_layer_slice_epilogue_workspace_bytes(M, max(3 * self.Hl, self.Il, self.Hs)),
-                  B.tp_layer_gemm_workspace_bytes(dtype, M, max(3 * H, I), max(self.Hs, self.Il)), 256)
+        Hs, Hl, Il = self.Hs, self.Hl, self.Il
+        gemm_shapes = [(M, 3 * H, Hs), (M, H, Hl), (M, I, Hs), (M, H, Il),          # forward partial products
+                       (M, Il, H), (Il, H, M), (M, Hs, I), (Hs, I, M),              # data and weight gradients
+                       (M, Hl, H), (Hl, H, M), (M, Hs, 3 * H), (Hs, 3 * H, M)]
+        nws = max(B.tp_layer_ln_apply_workspace_bytes(M, Hs),
+                  B.tp_layer_slice_epilogue_workspace_bytes(M, max(3 * Hl, Il, Hs)),
+                  max(B.tp_layer_gemm_workspace_bytes(dtype, *g) for g in gemm_shapes), 256)
         self.ws = torch.empty(nws, dtype=torch.uint8, device=device)
         self.grads = {k: e(*s) for k, s in PARAM_SHAPES(H, self.Hs, self.Hl, I, self.Il).items()}
 

@@ -25,19 +25,17 @@ GEMM_SHAPES = [(256, 256, 64), (520, 264, 136), (1000, 776, 2056), (64, 1536, 40
 
 # bf16 runs once per tile variant of the MFMA kernel (forced through TPL_GEMM_TILE) and once with the
 # library's own choice; float has a single kernel.
-@pytest.mark.parametrize("dtype,tile", [("bf16", None), ("bf16", "0"), ("bf16", "1"), ("bf16", "2"), ("bf16", "3"), ("bf16", "4"), ("f32", None)])
-@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
-@pytest.mark.parametrize("epi", ["none", "bias", "bias_resid", "gelu", "dgelu"])
-def test_gemm_variants(dtype, tile, ta, tb, epi, monkeypatch):
+def _check_gemms(dtype, tile, shares, ta, tb, epi, shapes, monkeypatch):
     import torch
     import paper_2111_05972_amd as pkg
-    if tile is None:
-        monkeypatch.delenv("TPL_GEMM_TILE", raising=False)
-    else:
-        monkeypatch.setenv("TPL_GEMM_TILE", tile)
+    for name, val in (("TPL_GEMM_TILE", tile), ("TPL_GEMM_SHARES", shares)):
+        if val is None:
+            monkeypatch.delenv(name, raising=False)
+        else:
+            monkeypatch.setenv(name, val)
     dt = pkg.TPL_BF16 if dtype == "bf16" else pkg.TPL_F32
     tol = 2e-2 if dtype == "bf16" else 1e-4
-    for si, (M, N, K) in enumerate(GEMM_SHAPES):
+    for si, (M, N, K) in enumerate(shapes):
         print(f"\n[gemm] {dtype} ta={ta} tb={tb} epi={epi} M={M} N={N} K={K}", flush=True)
         A = _draw(100 + si, (K, M) if ta else (M, K), 1.0, dtype)
         B = _draw(200 + si, (N, K) if tb else (K, N), 0.05, dtype)
@@ -74,6 +72,37 @@ def test_gemm_variants(dtype, tile, ta, tb, epi, monkeypatch):
         assert err <= tol, (M, N, K, err)
         if ref_aux is not None:
             assert oracle.max_rel_err(aux.float().cpu().numpy(), ref_aux) <= tol
+
+
+@pytest.mark.parametrize("dtype,tile", [("bf16", None), ("bf16", "0"), ("bf16", "1"), ("bf16", "2"), ("bf16", "3"), ("bf16", "4"), ("f32", None)])
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("epi", ["none", "bias", "bias_resid", "gelu", "dgelu"])
+def test_gemm_variants(dtype, tile, ta, tb, epi, monkeypatch):
+    _check_gemms(dtype, tile, None, ta, tb, epi, GEMM_SHAPES, monkeypatch)
+
+
+# K cut into shares (one workgroup per tile and share, partial sums added in share order by a second kernel):
+# forced share counts on every tile variant, K not a multiple of the share length, a share count above the
+# number of k-steps, and the library's own choice on a few-tiles / long-K shape where it splits by itself.
+SPLIT_SHAPES = [(256, 192, 520), (520, 264, 1096), (264, 512, 72), (8, 8, 8), (1000, 776, 2056)]
+
+
+@pytest.mark.parametrize("tile", [None, "0", "1", "2", "3", "4"])
+@pytest.mark.parametrize("shares", ["2", "5"])
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("epi", ["none", "bias_resid", "gelu", "dgelu"])
+def test_gemm_k_shares(tile, shares, ta, tb, epi, monkeypatch):
+    _check_gemms("bf16", tile, shares, ta, tb, epi, SPLIT_SHAPES, monkeypatch)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0)])
+def test_gemm_k_shares_own_choice(ta, tb, monkeypatch):
+    import paper_2111_05972_amd as pkg
+    monkeypatch.delenv("TPL_GEMM_TILE", raising=False)
+    monkeypatch.delenv("TPL_GEMM_SHARES", raising=False)
+    M, N, K = 512, 384, 8200
+    assert pkg.tp_layer_gemm_workspace_bytes(pkg.TPL_BF16, M, N, K) >= 2 * M * N * 4     # it does split
+    _check_gemms("bf16", None, None, ta, tb, "bias_resid", [(M, N, K)], monkeypatch)
 
 
 ATTN_CASES = [(2, 128, 2, 64), (1, 300, 3, 128), (3, 77, 2, 32), (1, 1, 4, 64), (2, 513, 1, 64), (1, 1024, 2, 128)]
