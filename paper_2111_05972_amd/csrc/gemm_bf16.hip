@@ -49,6 +49,7 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
@@ -108,17 +109,19 @@ __device__ __forceinline__ int swz_k32(int row) { return (row >> 2) & 3; }
 //    64-byte group further (cyclically over the row's 6 groups; 6 = 2 mod 4 keeps the four distinct).
 template <int R> __device__ __forceinline__ int mn_swz(int c, int k) {
     constexpr int CPR = R / 8;
-    if ((CPR & (CPR - 1)) == 0) return c ^ ((k & 3) << 2);
+    const int half = ((k >> 3) & 1) << 1;       // k and k + 8 (16x16x32 fragments read both at once): other 32 bytes
+    if ((CPR & (CPR - 1)) == 0) return c ^ ((k & 3) << 2) ^ half;
     int g = (c >> 2) + ((k >> 1) & 1);
     g = g >= CPR / 4 ? g - CPR / 4 : g;
-    return (g << 2) | (c & 3);
+    return (g << 2) | ((c & 3) ^ half);
 }
 template <int R> __device__ __forceinline__ int mn_unswz(int c, int k) {
     constexpr int CPR = R / 8;
-    if ((CPR & (CPR - 1)) == 0) return c ^ ((k & 3) << 2);
+    const int half = ((k >> 3) & 1) << 1;
+    if ((CPR & (CPR - 1)) == 0) return c ^ ((k & 3) << 2) ^ half;
     int g = (c >> 2) - ((k >> 1) & 1);
     g = g < 0 ? g + CPR / 4 : g;
-    return (g << 2) | (c & 3);
+    return (g << 2) | ((c & 3) ^ half);
 }
 
 // Raw buffer descriptor over `bytes` bytes at p (stride 0): loads at offsets >= bytes return zero
@@ -141,6 +144,15 @@ __device__ __forceinline__ void buffer_load_lds_b128(i32x4 rsrc, unsigned lds_ad
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory", "m0");
 }
+
+// The same with a scalar byte offset added by the instruction (the k position of a stage), so that the
+// per-lane offset stays loop invariant and no vector arithmetic is spent per load.
+__device__ __forceinline__ void buffer_load_lds_b128_s(i32x4 rsrc, unsigned lds_addr, unsigned voffset, unsigned soffset) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory", "m0");
+}
+constexpr unsigned OOB_HALF = 0x80000000u;     // out of bounds for operands below 2 GiB, and no wrap when a
+                                               // scalar offset below 2 GiB is added
 
 // Byte offsets (relative to the operand base, for tile origin mn0 and k = 0) of the T 16-byte chunks
 // this lane fetches per stage (operand tile of R = 64 T rows); chunk j of wavefront w lands in LDS
@@ -183,6 +195,32 @@ __device__ __forceinline__ bf16x8 dma_frag(const char* tile, int mn_base, int ks
         int mn = mn_base + (lane & 16) + 4 * (l16 & 3);
         int kq = l16 >> 2;
         int kb = ks * 16 + 8 * (lane >> 5);
+        bf16x8 out;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int k = kb + 4 * h + kq;
+            int off = k * (R * 2) + (mn_swz<R>(mn >> 3, k) << 4) + (mn & 7) * 2;
+            s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(tile + off));
+            bf16x4 b = __builtin_bit_cast(bf16x4, v);
+            out[4 * h + 0] = b[0]; out[4 * h + 1] = b[1]; out[4 * h + 2] = b[2]; out[4 * h + 3] = b[3];
+        }
+        return out;
+    }
+}
+
+// LDS -> fragment of the 16x16x32 matrix instruction: rows mn_base + (lane % 16), k = 8*(lane/16) + 0..7 of
+// the 32-k stage.
+template <bool KMAJ, int R>
+__device__ __forceinline__ bf16x8 dma_frag16(const char* tile, int mn_base, int lane) {
+    if (KMAJ) {
+        int row = mn_base + (lane & 15);
+        int c = lane >> 4;
+        return *reinterpret_cast<const bf16x8*>(tile + row * 64 + ((c ^ swz_k32(row)) << 4));
+    } else {
+        int l16 = lane & 15;
+        int mn = mn_base + 4 * (l16 & 3);
+        int kq = l16 >> 2;
+        int kb = 8 * (lane >> 4);
         bf16x8 out;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -239,10 +277,12 @@ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, 
     tn = within / rows;
 }
 
-// Epilogue of one wavefront: accumulators -> its LDS staging area -> 16-byte row accesses.
-template <typename TL>
-__device__ __forceinline__ void epilogue(const GemmParams& p, const f32x16 (&acc)[TL::TM][TL::TN], char* smem,
-                                         int wave, int lane, int m0, int n0, float* partial) {
+// Epilogue of one wavefront: accumulators -> its LDS staging area -> 16-byte row accesses.  The wavefront's
+// part of the tile goes through the staging area in slabs of 32 rows; store_slab(i, stage) writes slab i
+// (row r, column c of the wavefront's part at stage + r * EROW + 4 c).
+template <typename TL, typename StoreSlab>
+__device__ __forceinline__ void epilogue_rows(const GemmParams& p, char* smem, int wave, int lane, int m0, int n0,
+                                              float* partial, StoreSlab store_slab) {
     constexpr int TM = TL::TM, TN = TL::TN;
     const int wm = wave >> 1, wn = wave & 1;
     constexpr int LPR = TN * 4;               // lanes per staged row (8 columns each)
@@ -255,14 +295,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const f32x16 (&acc
     if (p.bias && !partial && gn < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + gn), bias8);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        // accumulator register v of block (i,j): row (v/4)*8 + (lane/32)*4 + v%4, column j*32 + lane%32
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int row = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                *reinterpret_cast<float*>(stage + row * TL::EROW + (j * 32 + (lane & 31)) * 4) = acc[i][j][v];
-            }
+        store_slab(i, stage);
 #pragma unroll
         for (int pass = 0; pass < PASSES; ++pass) {
             const int row = pass * RPP + er;
@@ -299,6 +332,37 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, const f32x16 (&acc
             }
         }
     }
+}
+
+// 32x32x16 accumulators: register v of block (i,j) is row (v/4)*8 + (lane/32)*4 + v%4, column j*32 + lane%32.
+template <typename TL>
+__device__ __forceinline__ void epilogue(const GemmParams& p, const f32x16 (&acc)[TL::TM][TL::TN], char* smem,
+                                         int wave, int lane, int m0, int n0, float* partial) {
+    epilogue_rows<TL>(p, smem, wave, lane, m0, n0, partial, [&](int i, char* stage) {
+#pragma unroll
+        for (int j = 0; j < TL::TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+                *reinterpret_cast<float*>(stage + row * TL::EROW + (j * 32 + (lane & 31)) * 4) = acc[i][j][v];
+            }
+    });
+}
+// 16x16x32 accumulators: register v of block (i,j) is row i*16 + (lane/16)*4 + v, column j*16 + lane%16.
+template <typename TL>
+__device__ __forceinline__ void epilogue16(const GemmParams& p, const f32x4 (&acc)[2 * TL::TM][2 * TL::TN], char* smem,
+                                           int wave, int lane, int m0, int n0, float* partial) {
+    epilogue_rows<TL>(p, smem, wave, lane, m0, n0, partial, [&](int i, char* stage) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int j = 0; j < 2 * TL::TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    int row = ii * 16 + (lane >> 4) * 4 + v;
+                    *reinterpret_cast<float*>(stage + row * TL::EROW + (j * 16 + (lane & 15)) * 4) = acc[2 * i + ii][j][v];
+                }
+    });
 }
 
 template <typename TL, bool A_KMAJ, bool B_KMAJ>
@@ -413,6 +477,185 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     epilogue<TL>(p, acc, smem, wave, lane, m0, n0, sh.partial);
+}
+
+// =================================================================================================
+// Eight wavefronts on the 16x16x32 matrix instruction: 4 x 2 wavefronts, two per SIMD, each owning
+// (2 TM) x (2 TN) blocks of 16 x 16 (64 x 96 of a 256 x 192 tile).
+// Why this instruction.  For random operands the chip runs these GEMMs at its power limit, and the 16x16x32
+// form needs less energy per flop than 32x32x16 (a pure matrix-instruction loop on random data sustains about
+// 15 % more with it: each instruction carries 32 k, so the float accumulators are read and written half as
+// often per flop).  What it costs is twice the fragment registers per k and matrix instructions of only 16
+// cycles: issuing a 1 KiB memory instruction (fragment read or direct load) holds a wavefront for about 34
+// cycles (measured), so a single wavefront per SIMD that also feeds itself leaves the matrix pipe idle; with
+// two per SIMD one issues matrix instructions while the other is held.
+// Pipeline.  A stage of 32 k is one k-substep; one barrier per stage at its start makes stage kt+1 visible
+// (its fragments are read during the matrix instructions of stage kt) and frees the slot of stage kt (read
+// during stage kt-1) for stage kt+STAGES.  Wavefronts 0..3 fetch the A stage (2 TM blocks of 1 KiB each),
+// wavefronts 4..7 the B stage (TN blocks each); the lane's offset is loop invariant and the k position is
+// the scalar offset of the load, checked against the end of the K share only in the last few stages.
+// Where it is used.  Its fixed cost per tile is lower than that of the kernel with fetch-only wavefronts
+// and its time per k-step higher (K-major operands arrive as half cache lines in 32-k stages), so the host
+// picks it for short K.
+// =================================================================================================
+// acc += a b, the accumulator tied to one AGPR quad.  Written as assembly because the compiler otherwise
+// moves the four-register accumulators between registers around every matrix instruction.  No other
+// matrix or vector instruction touches an accumulator within a stage, so no wait states are needed between
+// these; the reader after the loop inserts them itself (mfma16_drain).
+__device__ __forceinline__ void mfma16_inplace(f32x4& acc, const bf16x8& a, const bf16x8& b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma16_drain() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
+
+template <int TM_, int TN_, int STAGES_>
+struct Tile8 {
+    static constexpr int TM = TM_, TN = TN_, STAGES = STAGES_;          // 32-row / 32-column units per wavefront
+    static constexpr int BM = 4 * 32 * TM, BN = 2 * 32 * TN;
+    static constexpr int A_BYTES = BM * DK * 2, B_BYTES = BN * DK * 2;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LA = 2 * TM, LB = TN;                          // direct loads per stage of an A / B fetcher
+    static constexpr int LMAX = LA > LB ? LA : LB;
+    static constexpr int EROW = TN * 32 * 4 + 16, EWAVE = 32 * EROW;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES > 8 * EWAVE ? STAGES * STAGE_BYTES : 8 * EWAVE;
+    static_assert(STAGES * LMAX <= 63, "vmcnt is a 6-bit counter");
+};
+
+template <typename TL, bool A_KMAJ, bool B_KMAJ>
+__global__ __launch_bounds__(512) void gemm_bf16_x16w8_kernel(GemmParams p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int TM = TL::TM, TN = TL::TN, BM = TL::BM, BN = TL::BN, DSTAGES = TL::STAGES;
+    constexpr int FM = 2 * TM, FN = 2 * TN, NM = FM * FN;
+    constexpr int LA = TL::LA, LB = TL::LB, LMAX = TL::LMAX;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const bool is_a = wave_u < 4;                                 // which operand this wavefront fetches
+    const int wq = wave_u & 3;
+    const KShare sh = k_share(p, share_of_block(blockIdx.x, gridDim.x));
+    int tm, tn;
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    // fetch state of this wavefront: descriptor, LDS position of its first block inside a stage, bytes per k,
+    // per-lane offsets (rows / columns outside the matrix folded in) and the lane's k column (K-major only)
+    const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)(A_KMAJ ? p.M : p.K) * p.lda * 2));
+    const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
+    i32x4 rs;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) rs[q] = is_a ? ra[q] : rb[q];
+    const unsigned lds0 = (unsigned)(uintptr_t)(lds_void_ptr)smem;
+    const unsigned lds_first = lds0 + (is_a ? wq * LA * 1024 : TL::A_BYTES + wq * LB * 1024);
+    const unsigned kbytes = is_a ? (A_KMAJ ? 2u : (unsigned)p.lda * 2u) : (B_KMAJ ? 2u : (unsigned)p.ldb * 2u);
+    const int nload = is_a ? LA : LB;
+    unsigned vo[LMAX];
+    int kc = 0;
+    if (is_a) {
+        unsigned off[LA]; bool ok[LA];
+        dma_offsets<A_KMAJ, LA>(off, ok, kc, p.lda, m0, p.M, wq, lane);
+#pragma unroll
+        for (int d = 0; d < LMAX; ++d) vo[d] = d < LA ? ((A_KMAJ || ok[d < LA ? d : 0]) ? off[d < LA ? d : 0] : OOB_HALF) : OOB_HALF;
+        if (!A_KMAJ) kc = 0;
+    } else {
+        unsigned off[LB]; bool ok[LB];
+        dma_offsets<B_KMAJ, LB>(off, ok, kc, p.ldb, n0, p.N, wq, lane);
+#pragma unroll
+        for (int d = 0; d < LMAX; ++d) vo[d] = d < LB ? ((B_KMAJ || ok[d < LB ? d : 0]) ? off[d < LB ? d : 0] : OOB_HALF) : OOB_HALF;
+        if (!B_KMAJ) kc = 0;
+    }
+    // load d of stage s (of this K share); CHECKED: the stage may reach past the end of the share
+    auto dma_one = [&](int s, int d, auto checkedc) {
+        if (d >= LA && is_a) return;
+        if (d >= LB && !is_a) return;
+        const unsigned k0 = (unsigned)(sh.kt0 + s) * DK;
+        unsigned v = vo[d];
+        if (decltype(checkedc)::value) v = (int)k0 + kc < sh.kend ? v : OOB_HALF;
+        buffer_load_lds_b128_s(rs, lds_first + (s % DSTAGES) * TL::STAGE_BYTES + d * 1024, v, k0 * kbytes);
+    };
+    auto read_one = [&](bf16x8 (&fa)[FM], bf16x8 (&fb)[FN], int s, int r) {
+        const char* buf = smem + (s % DSTAGES) * TL::STAGE_BYTES;
+        if (r < FM) fa[r] = dma_frag16<A_KMAJ, BM>(buf, (wm * FM + r) * 16, lane);
+        else fb[r - FM] = dma_frag16<B_KMAJ, BN>(buf + TL::A_BYTES, (wn * FN + r - FM) * 16, lane);
+    };
+
+    f32x4 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
+
+    auto stage = [&](const bf16x8 (&fa)[FM], const bf16x8 (&fb)[FN], bf16x8 (&na)[FM], bf16x8 (&nb)[FN], int kt, auto checkedc) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int m = i * FN + j;
+                mfma16_inplace(acc[i][j], fa[i], fb[j]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (m < FM + FN) {
+                    read_one(na, nb, kt + 1, m);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int d = 0; d < LMAX; ++d)
+                    if (m == ((2 * d + 1) * NM) / (2 * LMAX)) {
+                        dma_one(kt + DSTAGES, d, checkedc);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            }
+    };
+    using Fast = std::integral_constant<bool, false>;
+    using Checked = std::integral_constant<bool, true>;
+    // loads this wavefront may leave in flight with stage s+1 landed: those of the D-2 newer stages
+    auto wait_stage = [&]() {
+        if (LA == LB) wait_vmcnt<(DSTAGES - 2) * LA>();
+        else if (is_a) wait_vmcnt<(DSTAGES - 2) * LA>();
+        else wait_vmcnt<(DSTAGES - 2) * LB>();
+    };
+
+#pragma unroll
+    for (int s0 = 0; s0 < DSTAGES; ++s0)
+#pragma unroll
+        for (int d = 0; d < LMAX; ++d) dma_one(s0, d, Checked{});
+    if (LA == LB) wait_vmcnt<(DSTAGES - 1) * LA>();              // stage 0 has landed
+    else if (is_a) wait_vmcnt<(DSTAGES - 1) * LA>();
+    else wait_vmcnt<(DSTAGES - 1) * LB>();
+    __builtin_amdgcn_s_barrier();
+    bf16x8 fa0[FM], fb0[FN], fa1[FM], fb1[FN];
+#pragma unroll
+    for (int r = 0; r < FM + FN; ++r) read_one(fa0, fb0, 0, r);
+    __builtin_amdgcn_sched_barrier(0);
+
+    auto sync = [&]() {
+        wait_stage();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    const int nfast = (sh.kend - sh.kt0 * DK) / DK - DSTAGES;
+    int kt = 0;
+    for (; kt + 1 < nfast; kt += 2) {
+        sync();
+        stage(fa0, fb0, fa1, fb1, kt, Fast{});
+        sync();
+        stage(fa1, fb1, fa0, fb0, kt + 1, Fast{});
+    }
+    for (; kt + 1 < sh.nk; kt += 2) {
+        sync();
+        stage(fa0, fb0, fa1, fb1, kt, Checked{});
+        sync();
+        stage(fa1, fb1, fa0, fb0, kt + 1, Checked{});
+    }
+    if (kt < sh.nk) {
+        sync();
+        stage(fa0, fb0, fa1, fb1, kt, Checked{});
+    }
+    mfma16_drain();
+    wait_vmcnt<0>();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    epilogue16<TL>(p, acc, smem, wave, lane, m0, n0, sh.partial);
 }
 
 // =================================================================================================
@@ -697,6 +940,30 @@ static hipError_t launch_layout(const GemmParams& p, const GemmArgs& a, int shar
     return launch<TL, false, false>(p, a, shares);
 }
 
+template <typename TL, bool AK, bool BK_>
+static hipError_t launch_w8(GemmParams p, const GemmArgs& a, int shares) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_x16w8_kernel<TL, AK, BK_>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    p.tiles_m = (int)((a.M + TL::BM - 1) / TL::BM);
+    p.tiles_n = (int)((a.N + TL::BN - 1) / TL::BN);
+    hipLaunchKernelGGL((gemm_bf16_x16w8_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(512),
+                       TL::LDS_BYTES, a.stream, p);
+    return hipGetLastError();
+}
+template <typename TL>
+static hipError_t launch_w8_layout(const GemmParams& p, const GemmArgs& a, int shares) {
+    const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
+    if (a_kmaj && b_kmaj) return launch_w8<TL, true, true>(p, a, shares);
+    if (a_kmaj && !b_kmaj) return launch_w8<TL, true, false>(p, a, shares);
+    if (!a_kmaj && b_kmaj) return launch_w8<TL, false, true>(p, a, shares);
+    return launch_w8<TL, false, false>(p, a, shares);
+}
+
 template <typename ST, bool AK, bool BK_>
 static hipError_t launch_spec(GemmParams p, const GemmArgs& a, int shares) {
     constexpr int LDS = ST::template lds_bytes<AK>();
@@ -740,7 +1007,7 @@ static int compute_units() {
     return cus;
 }
 
-constexpr int NVARIANTS = 5;
+constexpr int NVARIANTS = 6;
 constexpr int MAX_SHARES = 16;
 struct Plan { int variant, shares, nk_share; };
 
@@ -750,10 +1017,11 @@ struct Plan { int variant, shares, nk_share; };
 // partial sums to the workspace and a second kernel adds the shares in share order and applies the epilogue,
 // so the result does not depend on scheduling.  The estimate charges that second pass with its memory traffic.
 static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj) {
-    static const int bm[NVARIANTS] = {256, 256, 128, 192, 256}, bn[NVARIANTS] = {256, 192, 128, 192, 192};
-    static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2, 1};
-    static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658};
-    static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0};
+    // variant 5: 256 x 192 on 8 wavefronts and the 16x16x32 instruction
+    static const int bm[NVARIANTS] = {256, 256, 128, 192, 256, 256}, bn[NVARIANTS] = {256, 192, 128, 192, 192, 192};
+    static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2, 1, 1};
+    static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658, 0.70};
+    static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0, 12.5};
     const char* e = getenv("TPL_GEMM_TILE");          // tuning / test overrides: one digit; a number
     const int forced_v = (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) ? e[0] - '0' : -1;
     const char* es = getenv("TPL_GEMM_SHARES");
@@ -766,10 +1034,12 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj) {
         if (forced_v >= 0 && v != forced_v) continue;
         // the variant with fetch-only wavefronts is built for a K-major A (its MN-major A path spills)
         if (forced_v < 0 && v == 4 && !a_kmaj) continue;
+        // the 8-wavefront variant was measured against the others on K-major A only (forward, data gradients)
+        if (forced_v < 0 && v == 5 && !a_kmaj) continue;
         const int64_t tiles = ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]);
         for (int want = 1; want <= MAX_SHARES; ++want) {
             if (forced_s > 0 && want != (forced_s < MAX_SHARES ? forced_s : MAX_SHARES)) continue;
-            if (forced_s <= 0 && want > 1 && (tiles * (want - 1) >= cus || nk / want < 48)) break;
+            if (forced_s <= 0 && want > 1 && (tiles * (want - 1) >= cus || nk / want < 48 || v == 5)) break;
             int per = (nk + want - 1) / want;
             if (v == 4) per = (per + 1) & ~1;          // its wide A slots hold two k-steps: shares start on even steps
             const int shares = (nk + per - 1) / per;
@@ -816,6 +1086,7 @@ hipError_t gemm_bf16(const GemmArgs& a) {
         case 1: e = launch_layout<Tile<4, 3, 4>>(p, a, pl.shares); break;    // 256 x 192
         case 2: e = launch_layout<Tile<2, 2, 4>>(p, a, pl.shares); break;    // 128 x 128, two workgroups per CU
         case 3: e = launch_layout<Tile<3, 3, 3>>(p, a, pl.shares); break;    // 192 x 192, two workgroups per CU
+        case 5: e = launch_w8_layout<Tile8<2, 3, 5>>(p, a, pl.shares); break;      // 256 x 192, 8 wavefronts, 16x16x32
         default: e = launch_layout<Tile<4, 4, 4>>(p, a, pl.shares); break;   // 256 x 256
     }
     if (e != hipSuccess || pl.shares == 1) return e;
