@@ -157,7 +157,10 @@ constexpr unsigned OOB_HALF = 0x80000000u;     // out of bounds for operands bel
 // Byte offsets (relative to the operand base, for tile origin mn0 and k = 0) of the T 16-byte chunks
 // this lane fetches per stage (operand tile of R = 64 T rows); chunk j of wavefront w lands in LDS
 // block w*T + j (1 KiB blocks) at 16*lane.
-template <bool KMAJ, int T>
+// XOR16: MN-major chunk positions for the kernel that reads 16x16x32 fragments with per-lane base registers
+// (chunk c of row k at position c ^ xor16(k)); otherwise mn_swz.
+__device__ __forceinline__ int xor16(int k) { return (((k >> 1) & 1) << 1) | (((k >> 3) & 1) << 2); }
+template <bool KMAJ, int T, bool XOR16 = false>
 __device__ __forceinline__ void dma_offsets(unsigned (&off)[T], bool (&mn_ok)[T], int& kcol, int ld,
                                             int mn0, int MN, int wave, int lane) {
     constexpr int R = 64 * T;
@@ -173,7 +176,7 @@ __device__ __forceinline__ void dma_offsets(unsigned (&off)[T], bool (&mn_ok)[T]
         } else {
             int idx = block * 64 + lane;                    // physical chunk index inside the stage tile
             int k = idx / (R / 8);
-            int c = mn_unswz<R>(idx % (R / 8), k);          // logical chunk stored at that position
+            int c = XOR16 ? (idx % (R / 8)) ^ xor16(k) : mn_unswz<R>(idx % (R / 8), k);   // logical chunk stored there
             kcol = 0;
             mn_ok[j] = mn0 + c * 8 < MN;
             off[j] = (unsigned)(((int64_t)k * ld + mn0 + c * 8) * 2);
@@ -906,6 +909,191 @@ __global__ __launch_bounds__(256) void gemm_sum_shares_kernel(GemmParams p, int 
 }
 
 
+// =================================================================================================
+// Fetch and math wavefronts on the 16x16x32 matrix instruction (K-major A only): the tile, the rings and the
+// fetching wavefronts of the kernel above, the matrix instruction of the 8-wavefront kernel.  A math wavefront
+// owns 128 x 96 = 8 x 6 blocks: 192 accumulator registers of the 256 a wavefront has at two per SIMD, so
+// fragments cannot be double buffered.  The 6 B fragments of a k-step stay in registers; the 8 A fragments
+// (one per row of blocks, used for 6 consecutive instructions) rotate through four register sets, each refilled
+// two rows ahead of its use.  A B fragment is refilled with the next k-step's as soon as it is dead: the last
+// two rows are walked column by column, so B fragment j is dead after two instructions, and the next k-step
+// starts with two rows walked the same way, which gives every B fragment ten instructions (160 cycles) to
+// arrive.  Because the last fragment reads of k-step kt+1 are still in flight when k-step kt ends, the slot of
+// k-step kt is handed back to the fetching wavefronts one barrier later than above (at barrier kt+1), and the
+// fetch schedule is one k-step shorter: after barrier j, B k-step j+4 and (j even) the whole A unit j/2+2.
+// =================================================================================================
+__device__ __forceinline__ bf16x8 wide_frag16(const char* tile, int mn_base, int k32, int lane) {
+    int row = mn_base + (lane & 15);
+    int c = 4 * k32 + (lane >> 4);
+    return *reinterpret_cast<const bf16x8*>(tile + row * 128 + ((c ^ swz_k64(row)) << 4));
+}
+__device__ __forceinline__ void mfma16_v(f32x4& acc, const bf16x8& a, const bf16x8& b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
+template <typename ST, bool B_KMAJ>
+__global__ __launch_bounds__(512) void gemm_bf16_spec16_kernel(GemmParams p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int TM = ST::TM, TN = ST::TN, BM = ST::BM, BN = ST::BN, NB = ST::NB, NAW = ST::NA_WIDE;
+    constexpr int A_BYTES = ST::template a_bytes<true>();
+    constexpr int LA = 2 * TM, LBW = TN;                          // loads per fetching wavefront: A unit, B k-step
+    static_assert(NB == 5 && NAW == 3, "the fetch schedule below is written for these ring depths");
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const KShare sh = k_share(p, share_of_block(blockIdx.x, gridDim.x));   // sh.kt0 is even (host)
+    int tm, tn;
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    if (wave >= 4) {
+        // ---------------- fetching wavefronts ----------------
+        const int w = __builtin_amdgcn_readfirstlane(wave) & 3;
+        const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)p.M * p.lda * 2));
+        const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
+        const unsigned lds_a = (unsigned)(uintptr_t)(lds_void_ptr)smem, lds_b = lds_a + A_BYTES;
+        unsigned offb[TN];
+        bool okb[TN];
+        int kcb;
+        dma_offsets<B_KMAJ, TN, true>(offb, okb, kcb, p.ldb, n0, p.N, w, lane);
+        unsigned offw[LA];
+        int kcw[LA];
+#pragma unroll
+        for (int q = 0; q < LA; ++q) {
+            int row = (w * LA + q) * 8 + (lane >> 3);
+            int c = (lane & 7) ^ swz_k64(row);
+            kcw[q] = c * 8;
+            offw[q] = (unsigned)(((int64_t)(m0 + row) * p.lda + c * 8) * 2);
+        }
+        auto load_b = [&](int kt) {                               // k-step kt (of this K share) of B into its slot
+            const unsigned buf = lds_b + (kt % NB) * ST::B_SLOT;
+            const int k0 = (sh.kt0 + kt) * DK;
+            const unsigned step = B_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.ldb * 2);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                bool ok = B_KMAJ ? (k0 + kcb < sh.kend) : (okb[j] && k0 < sh.kend);
+                buffer_load_lds_b128(rb, buf + (w * TN + j) * 1024, ok ? offb[j] + step : OOB_OFFSET);
+            }
+        };
+        auto load_a = [&](int u) {                                // unit u (k-steps 2u, 2u+1 of this K share) of A
+            const unsigned buf = lds_a + (u % NAW) * ST::A_SLOT64;
+            const int ua = (sh.kt0 >> 1) + u;
+#pragma unroll
+            for (int q = 0; q < LA; ++q)
+                buffer_load_lds_b128(ra, buf + (w * LA + q) * 1024,
+                                     64 * ua + kcw[q] < sh.kend ? offw[q] + (unsigned)ua * 128u : OOB_OFFSET);
+        };
+        load_a(0); load_b(0); load_b(1); load_a(1); load_b(2); load_b(3);
+        wait_vmcnt<LA + 3 * LBW>();                               // unit 0 and B k-step 0 have landed
+        __builtin_amdgcn_s_barrier();
+        // At barrier kt k-step kt+1 must have landed.  Loads go out in batches after each barrier (the A unit,
+        // then the B k-step); the two newest batches, LA + 2 LBW loads, may still be in flight.
+        for (int kt = 0; kt < sh.nk; ++kt) {
+            wait_vmcnt<LA + 2 * LBW>();
+            __builtin_amdgcn_s_barrier();                         // k-step kt-1 has been read by everyone
+            if ((kt & 1) == 0) load_a((kt >> 1) + 2);
+            load_b(kt + NB - 1);
+        }
+        wait_vmcnt<0>();                                          // nothing lands in LDS during the epilogue
+        __builtin_amdgcn_s_barrier();
+        return;
+    }
+
+    // ---------------- math wavefronts ----------------
+    const int wm = wave >> 1, wn = wave & 1;
+    constexpr int FM = 2 * TM, FN = 2 * TN;
+    static_assert(FM >= 4, "head and tail pairs need four rows of blocks");
+    f32x4 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
+    static_assert(FM == 8, "the row schedule below is written for 8 rows of blocks");
+    bf16x8 fa[4], fb[FN];                                         // A fragments rotate through four registers sets
+    auto rd_a = [&](int kt, int row, int r) {                     // row `row` of k-step kt into set r
+        fa[r] = wide_frag16(smem + ((kt >> 1) % NAW) * ST::A_SLOT64, (wm * FM + row) * 16, kt & 1, lane);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // MN-major B (rows of BN values per k, chunk c of row k at position c ^ xor16(k)): fragment f = wn FN + j of
+    // the tile is chunks 2f, 2f+1; a lane reads rows k = 8 (lane/16) + 4 h + (lane%16)/4, h = 0, 1, whose xor16
+    // does not depend on h, so fragment f sits at bpos[(f ^ x) & 3] + 128 (f / 4) + 1536 h with x fixed per lane:
+    // four base registers, everything else immediates and scalars.
+    unsigned bpos[4];
+    int bq[FN], bs[FN];                                           // per fragment: which base, scalar byte offset
+    if (!B_KMAJ) {
+        const int k0 = 8 * (lane >> 4) + ((lane & 15) >> 2);
+        const int x = ((lane >> 3) & 1) | (((lane >> 4) & 1) << 1);
+        const unsigned base = (unsigned)(k0 * (BN * 2) + 8 * (lane & 1) + 16 * ((lane & 3) >> 1));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bpos[q] = base + 32u * (unsigned)((q + 2 * wn) & 3 ^ x);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) { bq[j] = j & 3; bs[j] = 128 * ((wn * FN + j) >> 2); }
+    }
+    auto rd_b = [&](int kt, int j) {
+        const char* slot = smem + A_BYTES + (kt % NB) * ST::B_SLOT;
+        if (B_KMAJ) {
+            fb[j] = dma_frag16<true, BN>(slot, (wn * FN + j) * 16, lane);
+        } else {
+            const char* src = slot + __builtin_amdgcn_readfirstlane(bs[j]) + bpos[bq[j]];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(src + h * 4 * (BN * 2)));
+                bf16x4 b4 = __builtin_bit_cast(bf16x4, v);
+                fb[j][4 * h + 0] = b4[0]; fb[j][4 * h + 1] = b4[1]; fb[j][4 * h + 2] = b4[2]; fb[j][4 * h + 3] = b4[3];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto mm = [&](int i, int r, int j) {                          // block (i, j) with the A fragment in set r
+        mfma16_v(acc[i][j], fa[r], fb[j]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // reads still in flight at the end of a k-step: the FN B fragments and 2 A fragments of its last lines
+    constexpr int TAIL_READS = (B_KMAJ ? FN : 2 * FN) + 2;
+    static_assert(TAIL_READS <= 15, "lgkmcnt is a 4-bit counter");
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) rd_a(0, r, r);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) rd_b(0, j);
+    // Row schedule of a k-step (sets 0..3 hold rows 0..3 at its start):
+    //   rows 0,1 column by column | read rows 4,5 -> sets 0,1 | row 2, read row 6 -> set 2 | row 3, read row 7 -> set 3
+    //   | row 4, read next row 0 -> set 0 | row 5, read next row 1 -> set 1
+    //   | rows 6,7 column by column, each B fragment refilled once both have used it | read next rows 2,3 -> sets 2,3
+    for (int kt = 0; kt < sh.nk; ++kt) {
+        asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(TAIL_READS) : "memory");   // every read of k-step kt-1's slots is done
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) { mm(0, 0, j); mm(1, 1, j); }
+        rd_a(kt, 4, 0);
+        rd_a(kt, 5, 1);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) mm(2, 2, j);
+        rd_a(kt, 6, 2);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) mm(3, 3, j);
+        rd_a(kt, 7, 3);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) mm(4, 0, j);
+        rd_a(kt + 1, 0, 0);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) mm(5, 1, j);
+        rd_a(kt + 1, 1, 1);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            mm(6, 2, j); mm(7, 3, j);
+            rd_b(kt + 1, j);
+        }
+        rd_a(kt + 1, 2, 2);
+        rd_a(kt + 1, 3, 3);
+    }
+    mfma16_drain();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    epilogue16<ST>(p, acc, smem, wave, lane, m0, n0, sh.partial);
+}
+
 bool gemm_bf16_supported(const GemmArgs& a) {
     if (a.dtype != BF16) return false;
     if (a.M % 8 || a.N % 8 || a.K % 8) return false;
@@ -979,6 +1167,21 @@ static hipError_t launch_spec(GemmParams p, const GemmArgs& a, int shares) {
     hipLaunchKernelGGL((gemm_bf16_spec_kernel<ST, AK, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(512), LDS, a.stream, p);
     return hipGetLastError();
 }
+template <typename ST, bool BK_>
+static hipError_t launch_spec16(GemmParams p, const GemmArgs& a, int shares) {
+    constexpr int LDS = ST::template lds_bytes<true>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_spec16_kernel<ST, BK_>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    p.tiles_m = (int)((a.M + ST::BM - 1) / ST::BM);
+    p.tiles_n = (int)((a.N + ST::BN - 1) / ST::BN);
+    hipLaunchKernelGGL((gemm_bf16_spec16_kernel<ST, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(512), LDS, a.stream, p);
+    return hipGetLastError();
+}
 template <typename ST>
 static hipError_t launch_spec_layout(const GemmParams& p, const GemmArgs& a, int shares) {
     const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
@@ -1007,7 +1210,7 @@ static int compute_units() {
     return cus;
 }
 
-constexpr int NVARIANTS = 6;
+constexpr int NVARIANTS = 7;
 constexpr int MAX_SHARES = 16;
 struct Plan { int variant, shares, nk_share; };
 
@@ -1016,12 +1219,12 @@ struct Plan { int variant, shares, nk_share; };
 // cut into `shares` equal runs of k-steps, one workgroup per (tile, share); every workgroup writes its float
 // partial sums to the workspace and a second kernel adds the shares in share order and applies the epilogue,
 // so the result does not depend on scheduling.  The estimate charges that second pass with its memory traffic.
-static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj) {
-    // variant 5: 256 x 192 on 8 wavefronts and the 16x16x32 instruction
-    static const int bm[NVARIANTS] = {256, 256, 128, 192, 256, 256}, bn[NVARIANTS] = {256, 192, 128, 192, 192, 192};
-    static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2, 1, 1};
-    static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658, 0.70};
-    static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0, 12.5};
+static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj) {
+    // variant 5: 256 x 192 on 8 wavefronts and the 16x16x32 instruction; 6: fetch and math wavefronts on 16x16x32
+    static const int bm[NVARIANTS] = {256, 256, 128, 192, 256, 256, 256}, bn[NVARIANTS] = {256, 192, 128, 192, 192, 192, 192};
+    static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2, 1, 1, 1};
+    static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658, 0.70, 0.602};
+    static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0, 12.5, 18.0};
     const char* e = getenv("TPL_GEMM_TILE");          // tuning / test overrides: one digit; a number
     const int forced_v = (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) ? e[0] - '0' : -1;
     const char* es = getenv("TPL_GEMM_SHARES");
@@ -1034,6 +1237,9 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj) {
         if (forced_v >= 0 && v != forced_v) continue;
         // the variant with fetch-only wavefronts is built for a K-major A (its MN-major A path spills)
         if (forced_v < 0 && v == 4 && !a_kmaj) continue;
+        if (v == 6 && !a_kmaj) continue;              // written for a K-major A only
+        // with an MN-major B its 20 fragment reads per k-step hold up the matrix instructions: no gain there
+        if (forced_v < 0 && v == 6 && !b_kmaj) continue;
         // the 8-wavefront variant was measured against the others on K-major A only (forward, data gradients)
         if (forced_v < 0 && v == 5 && !a_kmaj) continue;
         const int64_t tiles = ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]);
@@ -1041,7 +1247,7 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj) {
             if (forced_s > 0 && want != (forced_s < MAX_SHARES ? forced_s : MAX_SHARES)) continue;
             if (forced_s <= 0 && want > 1 && (tiles * (want - 1) >= cus || nk / want < 48 || v == 5)) break;
             int per = (nk + want - 1) / want;
-            if (v == 4) per = (per + 1) & ~1;          // its wide A slots hold two k-steps: shares start on even steps
+            if (v == 4 || v == 6) per = (per + 1) & ~1;          // its wide A slots hold two k-steps: shares start on even steps
             const int shares = (nk + per - 1) / per;
             if (forced_s <= 0 && shares != want) continue;   // the same plan as a smaller `want`
             const double per_cu = (double)((tiles * shares + cus - 1) / cus);
@@ -1055,8 +1261,8 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj) {
 
 size_t gemm_bf16_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     size_t need = 0;
-    for (int a_kmaj = 0; a_kmaj < 2; ++a_kmaj) {
-        const Plan pl = make_plan(M, N, K, a_kmaj != 0);
+    for (int layout = 0; layout < 4; ++layout) {
+        const Plan pl = make_plan(M, N, K, (layout & 1) != 0, (layout & 2) != 0);
         if (pl.shares > 1) need = std::max(need, (size_t)pl.shares * (size_t)M * (size_t)N * sizeof(float));
     }
     return need;
@@ -1071,7 +1277,7 @@ hipError_t gemm_bf16(const GemmArgs& a) {
     p.ldb = a.trans_b ? (int)a.K : (int)a.N;
     p.epi = a.epi;
     p.tiles_m = p.tiles_n = 0;
-    const Plan pl = make_plan(a.M, a.N, a.K, !a.trans_a);
+    const Plan pl = make_plan(a.M, a.N, a.K, !a.trans_a, a.trans_b != 0);
     p.nk_total = (int)((a.K + DK - 1) / DK);
     p.nk = pl.nk_share;
     p.partial = nullptr;
@@ -1087,6 +1293,10 @@ hipError_t gemm_bf16(const GemmArgs& a) {
         case 2: e = launch_layout<Tile<2, 2, 4>>(p, a, pl.shares); break;    // 128 x 128, two workgroups per CU
         case 3: e = launch_layout<Tile<3, 3, 3>>(p, a, pl.shares); break;    // 192 x 192, two workgroups per CU
         case 5: e = launch_w8_layout<Tile8<2, 3, 5>>(p, a, pl.shares); break;      // 256 x 192, 8 wavefronts, 16x16x32
+        case 6:                                                                    // 256 x 192, fetch + math, 16x16x32
+            e = a.trans_b ? launch_spec16<SpecTile<4, 3>, true>(p, a, pl.shares)
+                          : launch_spec16<SpecTile<4, 3>, false>(p, a, pl.shares);
+            break;
         default: e = launch_layout<Tile<4, 4, 4>>(p, a, pl.shares); break;   // 256 x 256
     }
     if (e != hipSuccess || pl.shares == 1) return e;
