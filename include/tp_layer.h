@@ -27,11 +27,16 @@
  * caption of Fig. 7).  TPL_ROW_EPILOGUE marks that rank: it adds b_o / b_dn and the residual
  * input to its partial sums, and in backward receives db_o, db_dn and adds dy to its partial dx.
  *
- * Ownership.  The caller owns every buffer, including `saved` and `ws`; the library allocates
- * nothing, never synchronises, and enqueues all work on `hip_stream` (a hipStream_t passed as
- * void*; NULL = the default stream).  Pointers must be 16-byte aligned.  Outputs must not alias
- * inputs.  Gradients are overwritten, not accumulated.  `ws` contents need not be preserved
- * between calls; calls that share a `ws` must be stream-ordered.
+ * Ownership.  The caller owns every buffer, including `saved` and `ws`; the library allocates no
+ * device memory, never synchronises with the host, and orders all work on `hip_stream` (a
+ * hipStream_t passed as void*; NULL = the default stream): work enqueued on `hip_stream` before a
+ * call happens before it, work enqueued after the call happens after it.  Inside tp_layer_fwd and
+ * tp_layer_bwd the attention block and the MLP block, which share no tensor, run as two chains,
+ * the second on a stream the library creates once per device (default priority) and forks from /
+ * joins to `hip_stream` with events; TPL_SINGLE_STREAM=1 in the environment keeps everything on
+ * `hip_stream`.  Pointers must be 16-byte aligned.  Outputs must not alias inputs.  Gradients are
+ * overwritten, not accumulated.  `ws` contents need not be preserved between calls; calls that
+ * share a `ws` must be stream-ordered.
  *
  * Errors.  Every entry point returns a tpl_status and never aborts; arguments are validated
  * before anything is enqueued.

@@ -3,6 +3,7 @@
 #include "../../include/tp_layer.h"
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "kernels.h"
 
@@ -63,8 +64,8 @@ size_t gemm_ws(int dtype, int64_t M, int64_t N, int64_t K) {
     return dtype == TPL_BF16 ? up(gemm_bf16_workspace_bytes(M, N, K)) : 0;
 }
 
-// Backward scratch: dU, dO, dQKV, D, column-sum partials, GEMM scratch.
-struct BwdWs { size_t du, d_o, dqkv, dsum, colsum, gemm, total; };
+// Backward scratch: dU, dO, dQKV, D, and per chain (attention, MLP) column-sum partials and GEMM scratch.
+struct BwdWs { size_t du, d_o, dqkv, dsum, colsum, colsum2, gemm, gemm2, gemm_each, total; };
 
 size_t fwd_gemm_ws(const Dims& x) {
     size_t g = 0;
@@ -83,6 +84,7 @@ void bwd_layout(const Dims& x, BwdWs* W) {
     W->dsum = off; off += up((size_t)x.B * x.nl * x.S * sizeof(float));
     int64_t nmax = std::max(std::max(x.Il, 3 * x.Hl), x.H);
     W->colsum = off; off += up(colsum_scratch_bytes(x.M, nmax));
+    W->colsum2 = off; off += up(colsum_scratch_bytes(x.M, nmax));
     size_t g = fwd_gemm_ws(x);   // dgrad shapes are the forward shapes with N and K swapped
     g = std::max(g, gemm_ws(x.dtype, x.M, x.Hl, x.H));
     g = std::max(g, gemm_ws(x.dtype, x.M, x.H, 3 * x.Hl));
@@ -90,7 +92,9 @@ void bwd_layout(const Dims& x, BwdWs* W) {
     g = std::max(g, gemm_ws(x.dtype, x.H, x.Il, x.M));
     g = std::max(g, gemm_ws(x.dtype, x.Hl, x.H, x.M));
     g = std::max(g, gemm_ws(x.dtype, x.H, 3 * x.Hl, x.M));
+    W->gemm_each = g;
     W->gemm = off; off += g;
+    W->gemm2 = off; off += g;
     W->total = off;
 }
 
@@ -104,6 +108,49 @@ struct GemmProfile {
     hipEvent_t start[CAP], stop[CAP];
     bool created[CAP] = {};
 } g_prof;
+
+// The attention block and the MLP block of one pass share no tensor (each has its own input, output and
+// gradients), so they are enqueued as two chains: the attention chain on the caller's stream and the MLP chain
+// on a second stream that the library creates once per device (default priority, non-blocking).  The second
+// stream is forked from the caller's stream and joined back to it with events, so the caller sees one pass on
+// its stream and the host never waits.  What the overlap buys: tiles of one chain fill the compute units the
+// other leaves idle (a GEMM whose tile count is below the number of compute units, the attention kernels,
+// the start and end of every kernel).  With per-GEMM timing on (tp_layer_profile) or TPL_SINGLE_STREAM=1 in
+// the environment everything runs on the caller's stream in the order written.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    int state = 0;       // 0 = not tried, 1 = ready, -1 = unavailable
+};
+constexpr int MAX_DEVICES = 64;
+SideStream g_side[MAX_DEVICES];
+
+// Returns the stream for the second chain, already waiting for everything enqueued on s so far; s itself when
+// the second stream is not used.
+hipStream_t side_fork(hipStream_t s) {
+    static const bool single = [] { const char* e = getenv("TPL_SINGLE_STREAM"); return e && e[0] == '1'; }();
+    if (single || g_prof.on) return s;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return s;
+    SideStream& ss = g_side[dev];
+    if (ss.state == 0) {
+        ss.state = (hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
+                    hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
+                    hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess) ? 1 : -1;
+    }
+    if (ss.state != 1) return s;
+    if (hipEventRecord(ss.fork, s) != hipSuccess || hipStreamWaitEvent(ss.stream, ss.fork, 0) != hipSuccess) return s;
+    return ss.stream;
+}
+// Makes s wait for everything enqueued on the second stream.
+int side_join(hipStream_t s, hipStream_t s2) {
+    if (s2 == s) return TPL_OK;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return TPL_EHIP;
+    SideStream& ss = g_side[dev];
+    if (hipEventRecord(ss.join, s2) != hipSuccess || hipStreamWaitEvent(s, ss.join, 0) != hipSuccess) return TPL_EHIP;
+    return TPL_OK;
+}
 
 int run_gemm(GemmArgs& g) {
     hipError_t e;
@@ -152,8 +199,20 @@ int fwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
     char* sv = (char*)saved;
     void *qkv = sv + L.qkv, *o = sv + L.o, *u = sv + L.u, *g = sv + L.g;
     float* lse = (float*)(sv + L.lse);
-    GemmScratch sc{ws, ws_bytes, s};
+    // each chain has its own half of the GEMM scratch
+    const size_t half = fwd_gemm_ws(x);
+    hipStream_t s2 = side_fork(s);
+    GemmScratch sc{ws, half, s}, sc2{(char*)ws + half, half, s2};
 
+    // MLP block (second chain): column-parallel up-projection + GeLU, row-parallel down-projection
+    GemmArgs g4 = mk(x, 0, 0, x.M, x.Il, x.H, x_mlp, p->w_up, g, sc2);
+    g4.bias = p->b_up; g4.aux = u; g4.epi = EPI_GELU;
+    if ((rc = run_gemm(g4))) return rc;
+    if (row_parallel) {
+        GemmArgs g5 = mk(x, 0, 0, x.M, x.H, x.Il, g, p->w_dn, y_mlp, sc2);
+        if (x.row_epi) { g5.bias = p->b_dn; g5.resid = x_mlp; }
+        if ((rc = run_gemm(g5))) return rc;
+    }
     // attention block: column-parallel fused QKV, attention on the local heads, row-parallel out-proj
     GemmArgs g1 = mk(x, 0, 0, x.M, 3 * x.Hl, x.H, x_attn, p->w_qkv, qkv, sc);
     g1.bias = p->b_qkv;
@@ -167,16 +226,7 @@ int fwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
         if (x.row_epi) { g3.bias = p->b_o; g3.resid = x_attn; }
         if ((rc = run_gemm(g3))) return rc;
     }
-    // MLP block: column-parallel up-projection + GeLU, row-parallel down-projection
-    GemmArgs g4 = mk(x, 0, 0, x.M, x.Il, x.H, x_mlp, p->w_up, g, sc);
-    g4.bias = p->b_up; g4.aux = u; g4.epi = EPI_GELU;
-    if ((rc = run_gemm(g4))) return rc;
-    if (row_parallel) {
-        GemmArgs g5 = mk(x, 0, 0, x.M, x.H, x.Il, g, p->w_dn, y_mlp, sc);
-        if (x.row_epi) { g5.bias = p->b_dn; g5.resid = x_mlp; }
-        if ((rc = run_gemm(g5))) return rc;
-    }
-    return TPL_OK;
+    return side_join(s, s2);
 }
 
 }  // namespace
@@ -205,7 +255,7 @@ int tp_layer_saved_offsets(const tp_layer_desc* desc, tp_layer_saved_layout* out
 size_t tp_layer_workspace_bytes(const tp_layer_desc* desc, int bwd) {
     Dims x;
     if (resolve(desc, &x) != TPL_OK) return 0;
-    if (!bwd) return fwd_gemm_ws(x);
+    if (!bwd) return 2 * fwd_gemm_ws(x);
     BwdWs W;
     bwd_layout(x, &W);
     return W.total;
@@ -223,7 +273,7 @@ int tp_layer_fwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     const void* ptrs[] = {x_attn, x_mlp, y_attn, y_mlp, saved, ws, p->w_qkv, p->b_qkv, p->w_o,
                           p->b_o, p->w_up, p->b_up, p->w_dn, p->b_dn};
     for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
-    if (ws_bytes < fwd_gemm_ws(x)) return TPL_EWORKSPACE;
+    if (ws_bytes < 2 * fwd_gemm_ws(x)) return TPL_EWORKSPACE;
     return fwd_impl(x, p, x_attn, x_mlp, y_attn, y_mlp, saved, ws, ws_bytes, (hipStream_t)hip_stream, true);
 }
 
@@ -253,24 +303,24 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     const void *qkv = sv + L.qkv, *o = sv + L.o, *u = sv + L.u, *g = sv + L.g;
     const float* lse = (const float*)(sv + L.lse);
     char* w = (char*)ws;
-    void *du = w + W.du, *d_o = w + W.d_o, *dqkv = w + W.dqkv, *gws = w + W.gemm;
-    float *dsum = (float*)(w + W.dsum), *cs = (float*)(w + W.colsum);
-    size_t gsz = W.total - W.gemm;
-    GemmScratch sc{gws, gsz, s};
+    void *du = w + W.du, *d_o = w + W.d_o, *dqkv = w + W.dqkv;
+    float *dsum = (float*)(w + W.dsum), *cs = (float*)(w + W.colsum), *cs2 = (float*)(w + W.colsum2);
+    hipStream_t s2 = side_fork(s);
+    GemmScratch sc{w + W.gemm, W.gemm_each, s}, sc2{w + W.gemm2, W.gemm_each, s2};
 
-    // MLP block.  dU = (dy_m W_dn^T) * gelu'(U) in one GEMM epilogue.
-    GemmArgs b5 = mk(x, 0, 1, x.M, x.Il, x.H, dy_mlp, p->w_dn, du, sc);
+    // MLP block (second chain).  dU = (dy_m W_dn^T) * gelu'(U) in one GEMM epilogue.
+    GemmArgs b5 = mk(x, 0, 1, x.M, x.Il, x.H, dy_mlp, p->w_dn, du, sc2);
     b5.aux = const_cast<void*>(u); b5.epi = EPI_DGELU;
     if ((rc = run_gemm(b5))) return rc;
-    GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, sc);
+    GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, sc2);
     if ((rc = run_gemm(w5))) return rc;
-    GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, sc);
+    GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, sc2);
     if ((rc = run_gemm(w4))) return rc;
-    if (colsum(x.dtype, x.M, x.Il, du, gr->db_up, cs, s) != hipSuccess) return TPL_EHIP;
-    GemmArgs d4 = mk(x, 0, 1, x.M, x.H, x.Il, du, p->w_up, dx_mlp, sc);
+    if (colsum(x.dtype, x.M, x.Il, du, gr->db_up, cs2, s2) != hipSuccess) return TPL_EHIP;
+    GemmArgs d4 = mk(x, 0, 1, x.M, x.H, x.Il, du, p->w_up, dx_mlp, sc2);
     if (x.row_epi) d4.resid = dy_mlp;
     if ((rc = run_gemm(d4))) return rc;
-    if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_mlp, gr->db_dn, cs, s) != hipSuccess) return TPL_EHIP;
+    if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_mlp, gr->db_dn, cs2, s2) != hipSuccess) return TPL_EHIP;
 
     // attention block
     GemmArgs d3 = mk(x, 0, 1, x.M, x.Hl, x.H, dy_attn, p->w_o, d_o, sc);
@@ -288,7 +338,8 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     if (colsum(x.dtype, x.M, 3 * x.Hl, dqkv, gr->db_qkv, cs, s) != hipSuccess) return TPL_EHIP;
     GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, sc);
     if (x.row_epi) d1.resid = dy_attn;
-    return run_gemm(d1);
+    if ((rc = run_gemm(d1))) return rc;
+    return side_join(s, s2);
 }
 
 size_t tp_layer_workspace_bytes_recompute(const tp_layer_desc* desc) {
