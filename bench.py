@@ -231,6 +231,9 @@ def main():
                     help="layer: tp_layer_fwd + tp_layer_bwd (the headline metric); layer-checkpoint: tp_layer_fwd + "
                          "tp_layer_bwd_recompute; ln: replicated LayerNorm forward + backward on the config's [M, H]; "
                          "memopt: one rank's local compute in the memory-optimised distribution at the config's widths")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="keep the attention and MLP chains of a pass on one stream (kernels then run one at a time: "
+                         "per-kernel profiles; the timed metric is the default two-chain schedule)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -239,6 +242,8 @@ def main():
               "--gpus above 1 is not supported (no collectives in this path)", file=sys.stderr)
         sys.exit(2)
 
+    if args.single_stream:
+        os.environ["TPL_SINGLE_STREAM"] = "1"     # read by the library at its first pass
     import numpy as np
     import torch
     import synthetic
