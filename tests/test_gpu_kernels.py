@@ -90,7 +90,7 @@ SPLIT_SHAPES = [(256, 192, 520), (520, 264, 1096), (264, 512, 72), (8, 8, 8), (1
 @pytest.mark.parametrize("tile", [None, "0", "1", "2", "3", "4", "5", "6"])
 @pytest.mark.parametrize("shares", ["2", "5"])
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
-@pytest.mark.parametrize("epi", ["none", "bias_resid", "gelu", "dgelu"])
+@pytest.mark.parametrize("epi", ["bias_resid", "gelu", "dgelu"])
 def test_gemm_k_shares(tile, shares, ta, tb, epi, monkeypatch):
     _check_gemms("bf16", tile, shares, ta, tb, epi, SPLIT_SHAPES, monkeypatch)
 
