@@ -34,7 +34,9 @@
  * tp_layer_bwd the attention block and the MLP block, which share no tensor, run as two chains,
  * the second on a stream the library creates once per device (default priority) and forks from /
  * joins to `hip_stream` with events; TPL_SINGLE_STREAM=1 in the environment keeps everything on
- * `hip_stream`.  Pointers must be 16-byte aligned.  Outputs must not alias inputs.  Gradients are
+ * `hip_stream`.  That second stream and its events are shared by all calls on a device: host
+ * threads that call tp_layer_fwd / tp_layer_bwd on the same device at the same time must
+ * serialise their calls (or set TPL_SINGLE_STREAM=1).  Pointers must be 16-byte aligned.  Outputs must not alias inputs.  Gradients are
  * overwritten, not accumulated.  `ws` contents need not be preserved between calls; calls that
  * share a `ws` must be stream-ordered.
  *

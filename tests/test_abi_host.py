@@ -118,3 +118,23 @@ def test_package_sharding_helper_matches_oracle_rule():
         a, b = pkg.shard_params(d, 2, r), oracle.shard_params(d, 2, r)
         for k in b:
             assert np.array_equal(np.asarray(a[k]), b[k]), k
+
+
+def test_gemm_workspace_follows_the_k_share_plan(monkeypatch):
+    """Host-side planning only: a GEMM with few tiles and a long K asks for float partial sums of whole shares,
+    a GEMM that fills the chip asks for the minimum, and a forced share count is honoured."""
+    monkeypatch.delenv("TPL_GEMM_TILE", raising=False)
+    monkeypatch.delenv("TPL_GEMM_SHARES", raising=False)
+    ws = lambda M, N, K: pkg.tp_layer_gemm_workspace_bytes(pkg.TPL_BF16, M, N, K)   # noqa: E731
+    few = ws(2048, 1536, 12288)                      # 64 tiles of 256 x 192 on 256 compute units
+    assert few % (2048 * 1536 * 4) == 0 and 2 <= few // (2048 * 1536 * 4) <= 16
+    assert ws(2048, 12288, 6144) == 256              # fills the chip: no split, minimum size
+    assert ws(2048, 1536, 1024) == 256               # K too short to share
+    monkeypatch.setenv("TPL_GEMM_SHARES", "3")
+    assert ws(512, 512, 4096) >= 3 * 512 * 512 * 4
+    # the layer's workspace covers the split GEMMs of both chains of a pass
+    monkeypatch.delenv("TPL_GEMM_SHARES", raising=False)
+    cfg = synthetic.get_config(5)
+    d = pkg.make_desc(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, pkg.TPL_BF16,
+                      cfg.causal, cfg.row_epilogue, cfg.head_dim, cfg.intermediate)
+    assert pkg.tp_layer_workspace_bytes(d, 1) >= 2 * few
