@@ -1094,6 +1094,188 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec16_kernel(GemmParams p) {
     epilogue16<ST>(p, acc, smem, wave, lane, m0, n0, sh.partial);
 }
 
+// =================================================================================================
+// 192 x 192, two workgroups per compute unit, on the 16x16x32 matrix instruction: the tile of the weight
+// gradients (short K, where co-resident workgroups hide each other's start and end) at the lower energy per flop
+// of this instruction.  Four wavefronts that fetch and compute; each owns 96 x 96 = 6 x 6 blocks, 144
+// accumulator registers, and since two workgroups share a SIMD's registers fragments are single buffered as in
+// the kernel above: six B fragments refilled in a column-wise tail, A fragments rotating through four register
+// sets.  The sets hold rows 0..3 at the start of a k-step and rows 2,3,0,1 of the next at its end, so two k-steps
+// (ROT = 0, 2) are unrolled.  One barrier per k-step, placed after the third row: by then every read of the
+// current stage has been issued (rows 4, 5 are fetched right after the first two rows), so the barrier frees this
+// stage's slot for stage kt+3 and makes stage kt+1 visible for the reads that follow it.
+// =================================================================================================
+template <typename TL, bool A_KMAJ, bool B_KMAJ>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_x16s_kernel(GemmParams p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int TM = TL::TM, TN = TL::TN, BM = TL::BM, BN = TL::BN, DSTAGES = TL::STAGES;
+    constexpr int FM = 2 * TM, FN = 2 * TN, L = TL::LOADS, LH = L / 2;
+    static_assert(FM == 6 && DSTAGES == 3 && L % 2 == 0, "row schedule and ring accounting are written for this tile");
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const KShare sh = k_share(p, share_of_block(blockIdx.x, gridDim.x));
+    const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)(A_KMAJ ? p.M : p.K) * p.lda * 2));
+    const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
+    const unsigned lds0 = (unsigned)(uintptr_t)(lds_void_ptr)smem;
+    int tm, tn;
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    f32x4 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
+
+    unsigned offa[TM], offb[TN];
+    bool oka[TM], okb[TN];
+    int kca, kcb;
+    dma_offsets<A_KMAJ, TM, true>(offa, oka, kca, p.lda, m0, p.M, wave, lane);
+    dma_offsets<B_KMAJ, TN, true>(offb, okb, kcb, p.ldb, n0, p.N, wave, lane);
+    // MN-major operands: the lane's offset is loop invariant (columns outside the matrix folded in), the k position
+    // is the load's scalar offset, and a stage past the end of the K share reads through a descriptor of zero
+    // records (everything out of bounds), so such a load costs no vector arithmetic at all.
+#pragma unroll
+    for (int d = 0; d < TM; ++d) if (!A_KMAJ) offa[d] = oka[d] ? offa[d] : OOB_HALF;
+#pragma unroll
+    for (int e = 0; e < TN; ++e) if (!B_KMAJ) offb[e] = okb[e] ? offb[e] : OOB_HALF;
+    auto dma_one = [&](int slot_off, int s, int d) {              // load d of stage s (of this K share) into its slot
+        const unsigned buf = lds0 + (unsigned)slot_off;
+        const int k0 = (sh.kt0 + s) * DK;
+        if (d < TM) {
+            const unsigned dst = buf + (wave_u * TM + d) * 1024;
+            if (A_KMAJ) {
+                buffer_load_lds_b128(ra, dst, k0 + kca < sh.kend ? offa[d] + (unsigned)k0 * 2u : OOB_OFFSET);
+            } else {
+                i32x4 r = ra;
+                r[2] = k0 < sh.kend ? ra[2] : 0;
+                buffer_load_lds_b128_s(r, dst, offa[d], (unsigned)k0 * (unsigned)p.lda * 2u);
+            }
+        } else {
+            const int e = d - TM;
+            const unsigned dst = buf + TL::A_BYTES + (wave_u * TN + e) * 1024;
+            if (B_KMAJ) {
+                buffer_load_lds_b128(rb, dst, k0 + kcb < sh.kend ? offb[e] + (unsigned)k0 * 2u : OOB_OFFSET);
+            } else {
+                i32x4 r = rb;
+                r[2] = k0 < sh.kend ? rb[2] : 0;
+                buffer_load_lds_b128_s(r, dst, offb[e], (unsigned)k0 * (unsigned)p.ldb * 2u);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    bf16x8 fa[4], fb[FN];
+    // MN-major operands use the xor16 chunk positions and four per-lane base registers (see the kernel above)
+    unsigned apos[4], bpos[4];
+    {
+        const int k0 = 8 * (lane >> 4) + ((lane & 15) >> 2);
+        const int x = ((lane >> 3) & 1) | (((lane >> 4) & 1) << 1);
+        const unsigned lane_off = (unsigned)(8 * (lane & 1) + 16 * ((lane & 3) >> 1));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            apos[q] = (unsigned)(k0 * (BM * 2)) + lane_off + 32u * (unsigned)(((q + 2 * wm) & 3) ^ x);
+            bpos[q] = (unsigned)(k0 * (BN * 2)) + lane_off + 32u * (unsigned)(((q + 2 * wn) & 3) ^ x);
+        }
+    }
+    auto rd_mn = [&](bf16x8& dst, const char* tile, const unsigned (&pos)[4], int w, int f, int R) {
+        const char* src = tile + __builtin_amdgcn_readfirstlane(128 * ((w * 6 + f) >> 2)) + pos[f & 3];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(src + h * 4 * (R * 2)));
+            bf16x4 b4 = __builtin_bit_cast(bf16x4, v);
+            dst[4 * h + 0] = b4[0]; dst[4 * h + 1] = b4[1]; dst[4 * h + 2] = b4[2]; dst[4 * h + 3] = b4[3];
+        }
+    };
+    auto rd_a = [&](int slot_off, int row, int r) {
+        const char* tile = smem + slot_off;
+        if (A_KMAJ) fa[r] = dma_frag16<true, BM>(tile, (wm * FM + row) * 16, lane);
+        else rd_mn(fa[r], tile, apos, wm, row, BM);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto rd_b = [&](int slot_off, int j) {
+        const char* tile = smem + slot_off + TL::A_BYTES;
+        if (B_KMAJ) fb[j] = dma_frag16<true, BN>(tile, (wn * FN + j) * 16, lane);
+        else rd_mn(fb[j], tile, bpos, wn, j, BN);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto mm = [&](int i, int r, int j) {
+        mfma16_v(acc[i][j], fa[r], fb[j]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // k-step kt with the A sets rotated by ROT (0 or 2): logical set q is register set (q + ROT) & 3.
+    // o0, o1, o2: byte offsets of the ring slots of stages kt, kt+1, kt+2 (stage kt+3 reuses o0).
+    auto stage = [&](int kt, int o0, int o1, int o2, auto rotc) {
+        constexpr int ROT = decltype(rotc)::value;
+        constexpr int S0 = ROT & 3, S1 = (1 + ROT) & 3, S2 = (2 + ROT) & 3, S3 = (3 + ROT) & 3;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {                            // rows 0, 1 column by column
+            mm(0, S0, j); mm(1, S1, j);
+            if (j == 1) dma_one(o2, kt + 2, LH);                  // second half of stage kt+2's loads
+            if (j == 3) dma_one(o2, kt + 2, LH + 1);
+        }
+        rd_a(o0, 4, S0);
+        rd_a(o0, 5, S1);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            mm(2, S2, j);
+            if (j == 1) dma_one(o2, kt + 2, LH + 2);
+        }
+        // every read of stage kt has been issued; stage kt+1 has landed once only stage kt+2's loads are in flight
+        wait_vmcnt<L>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        rd_a(o1, 0, S2);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            mm(3, S3, j);
+            if (j == 2) dma_one(o0, kt + 3, 0);                   // first half of stage kt+3's loads: slot of stage kt
+        }
+        rd_a(o1, 1, S3);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {                            // rows 4, 5 column by column; B refilled when dead
+            mm(4, S0, j); mm(5, S1, j);
+            rd_b(o1, j);
+            if (j == 1) dma_one(o0, kt + 3, 1);
+            if (j == 4) dma_one(o0, kt + 3, 2);
+        }
+        rd_a(o1, 2, S0);
+        rd_a(o1, 3, S1);
+    };
+    static_assert(LH == 3, "three loads before and three after the barrier of a k-step");
+    using R0 = std::integral_constant<int, 0>;
+    using R2 = std::integral_constant<int, 2>;
+    constexpr int SB = TL::STAGE_BYTES;
+
+#pragma unroll
+    for (int d = 0; d < L; ++d) dma_one(0, 0, d);
+#pragma unroll
+    for (int d = 0; d < L; ++d) dma_one(SB, 1, d);
+#pragma unroll
+    for (int d = 0; d < LH; ++d) dma_one(2 * SB, 2, d);
+    wait_vmcnt<L + LH>();                                        // stage 0 has landed
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) rd_a(0, r, r);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) rd_b(0, j);
+    int kt = 0, o0 = 0, o1 = SB, o2 = 2 * SB;                     // slots of stages kt, kt+1, kt+2 (scalars)
+    for (; kt + 1 < sh.nk; kt += 2) {
+        stage(kt, o0, o1, o2, R0{});
+        stage(kt + 1, o1, o2, o0, R2{});
+        const int t0 = o0; o0 = o2; o2 = o1; o1 = t0;             // two stages on: (o2, o0, o1)
+    }
+    if (kt < sh.nk) stage(kt, o0, o1, o2, R0{});
+    mfma16_drain();
+    wait_vmcnt<0>();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    epilogue16<TL>(p, acc, smem, wave, lane, m0, n0, sh.partial);
+}
+
 bool gemm_bf16_supported(const GemmArgs& a) {
     if (a.dtype != BF16) return false;
     if (a.M % 8 || a.N % 8 || a.K % 8) return false;
@@ -1126,6 +1308,30 @@ static hipError_t launch_layout(const GemmParams& p, const GemmArgs& a, int shar
     if (a_kmaj && !b_kmaj) return launch<TL, true, false>(p, a, shares);
     if (!a_kmaj && b_kmaj) return launch<TL, false, true>(p, a, shares);
     return launch<TL, false, false>(p, a, shares);
+}
+
+template <typename TL, bool AK, bool BK_>
+static hipError_t launch_x16s(GemmParams p, const GemmArgs& a, int shares) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_x16s_kernel<TL, AK, BK_>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    p.tiles_m = (int)((a.M + TL::BM - 1) / TL::BM);
+    p.tiles_n = (int)((a.N + TL::BN - 1) / TL::BN);
+    hipLaunchKernelGGL((gemm_bf16_x16s_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(256),
+                       TL::LDS_BYTES, a.stream, p);
+    return hipGetLastError();
+}
+template <typename TL>
+static hipError_t launch_x16s_layout(const GemmParams& p, const GemmArgs& a, int shares) {
+    const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
+    if (a_kmaj && b_kmaj) return launch_x16s<TL, true, true>(p, a, shares);
+    if (a_kmaj && !b_kmaj) return launch_x16s<TL, true, false>(p, a, shares);
+    if (!a_kmaj && b_kmaj) return launch_x16s<TL, false, true>(p, a, shares);
+    return launch_x16s<TL, false, false>(p, a, shares);
 }
 
 template <typename TL, bool AK, bool BK_>
@@ -1210,7 +1416,7 @@ static int compute_units() {
     return cus;
 }
 
-constexpr int NVARIANTS = 7;
+constexpr int NVARIANTS = 8;
 constexpr int MAX_SHARES = 16;
 struct Plan { int variant, shares, nk_share; };
 
@@ -1220,11 +1426,13 @@ struct Plan { int variant, shares, nk_share; };
 // partial sums to the workspace and a second kernel adds the shares in share order and applies the epilogue,
 // so the result does not depend on scheduling.  The estimate charges that second pass with its memory traffic.
 static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj) {
-    // variant 5: 256 x 192 on 8 wavefronts and the 16x16x32 instruction; 6: fetch and math wavefronts on 16x16x32
-    static const int bm[NVARIANTS] = {256, 256, 128, 192, 256, 256, 256}, bn[NVARIANTS] = {256, 192, 128, 192, 192, 192, 192};
-    static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2, 1, 1, 1};
-    static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658, 0.70, 0.602};
-    static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0, 12.5, 18.0};
+    // variant 5: 256 x 192 on 8 wavefronts and the 16x16x32 instruction; 6: fetch and math wavefronts on 16x16x32;
+    // 7: 192 x 192, two workgroups per compute unit, on 16x16x32
+    static const int bm[NVARIANTS] = {256, 256, 128, 192, 256, 256, 256, 192};
+    static const int bn[NVARIANTS] = {256, 192, 128, 192, 192, 192, 192, 192};
+    static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2, 1, 1, 1, 2};
+    static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658, 0.70, 0.602, 0.509};
+    static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0, 12.5, 18.0, 12.0};
     const char* e = getenv("TPL_GEMM_TILE");          // tuning / test overrides: one digit; a number
     const int forced_v = (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) ? e[0] - '0' : -1;
     const char* es = getenv("TPL_GEMM_SHARES");
@@ -1238,6 +1446,9 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj)
         // the variant with fetch-only wavefronts is built for a K-major A (its MN-major A path spills)
         if (forced_v < 0 && v == 4 && !a_kmaj) continue;
         if (v == 6 && !a_kmaj) continue;              // written for a K-major A only
+        // the two-per-CU 16x16x32 tile is the weight-gradient kernel (MN-major A); with a K-major A it only pays when
+        // many rounds of tiles amortise its cold starts (measured inside the layer step, not in an isolated loop)
+        if (forced_v < 0 && v == 7 && a_kmaj && ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]) < 4 * compute_units()) continue;
         // with an MN-major B its 20 fragment reads per k-step hold up the matrix instructions: no gain there
         if (forced_v < 0 && v == 6 && !b_kmaj) continue;
         // the 8-wavefront variant was measured against the others on K-major A only (forward, data gradients)
@@ -1293,6 +1504,7 @@ hipError_t gemm_bf16(const GemmArgs& a) {
         case 2: e = launch_layout<Tile<2, 2, 4>>(p, a, pl.shares); break;    // 128 x 128, two workgroups per CU
         case 3: e = launch_layout<Tile<3, 3, 3>>(p, a, pl.shares); break;    // 192 x 192, two workgroups per CU
         case 5: e = launch_w8_layout<Tile8<2, 3, 5>>(p, a, pl.shares); break;      // 256 x 192, 8 wavefronts, 16x16x32
+        case 7: e = launch_x16s_layout<Tile<3, 3, 3>>(p, a, pl.shares); break;     // 192 x 192, 2 workgroups/CU, 16x16x32
         case 6:                                                                    // 256 x 192, fetch + math, 16x16x32
             e = a.trans_b ? launch_spec16<SpecTile<4, 3>, true>(p, a, pl.shares)
                           : launch_spec16<SpecTile<4, 3>, false>(p, a, pl.shares);

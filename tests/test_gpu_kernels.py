@@ -74,7 +74,7 @@ def _check_gemms(dtype, tile, shares, ta, tb, epi, shapes, monkeypatch):
             assert oracle.max_rel_err(aux.float().cpu().numpy(), ref_aux) <= tol
 
 
-@pytest.mark.parametrize("dtype,tile", [("bf16", None), ("bf16", "0"), ("bf16", "1"), ("bf16", "2"), ("bf16", "3"), ("bf16", "4"), ("bf16", "5"), ("bf16", "6"), ("f32", None)])
+@pytest.mark.parametrize("dtype,tile", [("bf16", None), ("bf16", "0"), ("bf16", "1"), ("bf16", "2"), ("bf16", "3"), ("bf16", "4"), ("bf16", "5"), ("bf16", "6"), ("bf16", "7"), ("f32", None)])
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("epi", ["none", "bias", "bias_resid", "gelu", "dgelu"])
 def test_gemm_variants(dtype, tile, ta, tb, epi, monkeypatch):
@@ -87,7 +87,7 @@ def test_gemm_variants(dtype, tile, ta, tb, epi, monkeypatch):
 SPLIT_SHAPES = [(256, 192, 520), (520, 264, 1096), (264, 512, 72), (8, 8, 8), (1000, 776, 2056)]
 
 
-@pytest.mark.parametrize("tile", [None, "0", "1", "2", "3", "4", "5", "6"])
+@pytest.mark.parametrize("tile", [None, "0", "1", "2", "3", "4", "5", "6", "7"])
 @pytest.mark.parametrize("shares", ["2", "5"])
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("epi", ["bias_resid", "gelu", "dgelu"])
