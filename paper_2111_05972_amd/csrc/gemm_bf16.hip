@@ -1,38 +1,45 @@
 // bf16 GEMM for gfx950: C[M,N] = epi(opA(A) opB(B)), float accumulation on the matrix cores.
 //
-// Tile and pipeline.  A 256-thread workgroup (4 wavefronts, 2 x 2) owns a 256 x 256 output tile;
-// each wavefront accumulates 128 x 128 as 4 x 4 MFMA 32x32x16 blocks (256 accumulator registers).
-// Three smaller variants (256 x 192, 192 x 192, 128 x 128) exist for GEMMs whose 256 x 256 tile count
-// fills the last round over the compute units badly or whose K is short; the host picks by estimate.
-// K is walked in stages of 32 through a 4-deep LDS ring (4 x 32 KiB) that is filled by
-// buffer_load ... lds: global memory goes straight into LDS, no staging registers, and anything
-// outside the matrix is zero filled by the buffer bounds check.  Loads run about 3 stages ahead of
-// the math.  There is one barrier per stage, placed between the two 16-MFMA halves of the stage.
+// Kernels (the host picks one per GEMM by an estimate of its time, see make_plan):
+//   gemm_bf16_kernel          4 wavefronts that fetch and compute, MFMA 32x32x16; tiles 256x256, 256x192, and
+//                             192x192 / 128x128 with two workgroups per compute unit
+//   gemm_bf16_spec_kernel     256x192, 4 math + 4 fetch wavefronts, MFMA 32x32x16      (forward GEMMs: NN)
+//   gemm_bf16_spec16_kernel   the same roles on MFMA 16x16x32, K-major A               (data gradients: NT)
+//   gemm_bf16_x16s_kernel     192x192, two workgroups per compute unit, MFMA 16x16x32  (weight gradients: TN)
+//   gemm_bf16_x16w8_kernel    256x192, 8 wavefronts that fetch and compute, 16x16x32   (short K)
+//   gemm_sum_shares_kernel    adds the partial sums of a GEMM whose K was cut into shares, applies the epilogue
 //
-// Instruction order.  A global load costs the wavefront that issues it roughly 75 cycles in which
-// it issues no matrix instruction (measured; the same for loads into registers), and a burst of
-// loads costs the sum.  So the loop body is written as single pieces (one matrix instruction, one
-// fragment read, one direct load) separated by scheduling fences, with the loads of a stage spread
-// evenly over the two halves that follow the barrier which frees their slot.  A further variant
-// (256 x 192, 512 threads) takes the loads out of the math wavefronts altogether: four wavefronts
-// only fetch, four only compute (128 x 96 each, which is what fits the 256 registers a wavefront
-// has at two wavefronts per SIMD).
+// Pipeline.  K is walked in stages of 32 through LDS rings filled by buffer_load ... lds: global memory goes
+// straight into LDS, no staging registers, and anything outside the matrix is zero filled by the buffer bounds
+// check.  Loads run 2 to 4 stages ahead of the math; there is one workgroup barrier per stage.  The loop bodies
+// are written as single pieces (one matrix instruction, one fragment read, one direct load) separated by
+// scheduling fences, so the instruction order is the one written.
 //
-// Operand layouts.  Either operand may be stored with K contiguous ("K-major": A as [M,K], B as
-// [N,K]) or with its M/N dimension contiguous ("MN-major": A as [K,M], B as [K,N]).  K-major tiles
-// are read from LDS with 16-byte reads; MN-major tiles with the transposing ds_read_b64_tr_b16,
-// which hands each lane four K-consecutive values of one column, so no operand is ever transposed
-// in HBM or in registers.  LDS chunk positions are XOR-swizzled (applied on the global-address side
-// of the direct loads) so that both kinds of read are bank-conflict free.
+// What decides the design (measured on the device):
+//  * With random operands these GEMMs run at the board's power limit with the clock pulled down; throughput then
+//    follows energy per flop.  MFMA 16x16x32 needs less than 32x32x16 (each instruction carries 32 k, so the float
+//    accumulators are read and written half as often per flop): a pure matrix-instruction loop on random data
+//    sustains 15 % more with it.
+//  * Issuing a 1 KiB memory instruction (fragment read or direct load) holds a wavefront for about 35 cycles.  Under
+//    a 32-cycle 32x32x16 instruction that is almost hidden, under a 16-cycle 16x16x32 it is not.  Hence fetch-only
+//    wavefronts beside the math wavefronts, or two wavefronts per SIMD.
+//  * Two wavefronts per SIMD leave 256 registers each, 144 to 192 of them accumulators: the 16x16x32 kernels
+//    single-buffer their fragments and refill each register as soon as its last use of the k-step is issued.
 //
-// Scheduling over the chip.  One workgroup per output tile.  Workgroup ids are dealt round-robin to
-// the 8 XCDs (each with its own L2), so ids are regrouped to give every XCD a contiguous run of
-// tiles, and tiles are ordered column-major inside bands of 8 tile rows: the 32 tiles in flight on
-// an XCD form an 8 x 4 block that shares 12 operand panels in that XCD's L2.
+// Operand layouts.  Either operand may be stored with K contiguous ("K-major": A as [M,K], B as [N,K]) or with
+// its M/N dimension contiguous ("MN-major": A as [K,M], B as [K,N]).  K-major tiles are read from LDS with
+// 16-byte reads; MN-major tiles with the transposing ds_read_b64_tr_b16, which hands each lane four
+// K-consecutive values of one column, so no operand is ever transposed in HBM or in registers.  LDS chunk
+// positions are XOR-swizzled (applied on the global-address side of the direct loads) so that the reads are
+// free of bank conflicts; the XOR depends on the fragment shape that reads the tile.
 //
-// Epilogue.  Accumulators go through per-wavefront LDS staging so that every global access of the
-// epilogue (bias, residual, GeLU input, output) is a 16-byte access and 16 lanes cover 256
-// contiguous bytes of a row.
+// Scheduling over the chip.  One workgroup per (output tile, K share).  Workgroup ids are dealt round-robin to
+// the 8 XCDs (each with its own L2), so ids are regrouped to give every XCD a contiguous run of tiles, and tiles
+// are ordered column-major inside bands of 8 tile rows: the tiles in flight on an XCD share operand panels in
+// that XCD's L2.
+//
+// Epilogue.  Accumulators go through per-wavefront LDS staging so that every global access of the epilogue
+// (bias, residual, GeLU input, output) is a 16-byte access and a staged row is contiguous.
 #include <hip/hip_runtime.h>
 #include <type_traits>
 
