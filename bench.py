@@ -87,7 +87,7 @@ def bench_layernorm(args, cfg, dt, pkg, torch, synthetic):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"LayerNorm on [M={M}, H={H}] of config {cfg.cfg_id}: {cfg.name}"},
-        "roofline": {"kernel": "ln_fwd_kernel + ln_bwd_kernel", "bound": "hbm",
+        "roofline": {"kernel": "ln_fwd_kernel + ln_bwd_fused_kernel", "bound": "hbm",
                      "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbs / 8000.0, 4),
                      "traffic": None, "fwd": {"ms": round(fwd_ms, 4), "GBps": round(fwd_bytes / fwd_ms / 1e6, 1)},
                      "bwd": {"ms": round(bwd_ms, 4), "GBps": round(bwd_bytes / bwd_ms / 1e6, 1)}},

@@ -5,9 +5,12 @@
 // accesses, up to 8 chunks of 8 elements per thread: H <= 16384), so every tensor is read or written
 // exactly once:
 //   forward : reads a (and b), writes z = a + b (optional) and y          -> up to 4 M H elements
-//   backward: a row pass reads dy, z for the two per-row means; a tile pass (32 rows x 512 columns per
-//             workgroup) reads dy, z again (served by the infinity cache), writes dz and per-slab column
-//             partials of dgamma, dbeta, which a small kernel sums in slab order (deterministic).
+//   backward: one kernel; a workgroup walks its rows (row, row + G, ...) holding dy and z of a row in registers
+//             (next row prefetched), reduces the two per-row means, writes dz, and accumulates its column
+//             sums of dgamma, dbeta in registers; the G per-workgroup partials are then summed in workgroup
+//             order by a small kernel (deterministic)                         -> 3 M H elements + 4 G H floats
+//   (the distributed variant below keeps the older two-pass form: row sums first, because there the
+//   caller all-reduces them between the passes)
 #include <hip/hip_runtime.h>
 
 #include "device_math.h"
@@ -18,6 +21,7 @@ namespace tpl {
 constexpr int LN_THREADS = 256;
 
 // Sum over the workgroup, same value returned to every thread; fixed combination order.
+template <int NW = 4>
 __device__ __forceinline__ float block_sum(float v, float* red) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -25,7 +29,10 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
     __syncthreads();                   // red may still be read from the previous reduction
     if ((threadIdx.x & 63) == 0) red[w] = v;
     __syncthreads();
-    return ((red[0] + red[1]) + red[2]) + red[3];
+    float s = red[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) s += red[i];
+    return s;
 }
 
 template <typename T, int MAXC>
@@ -183,11 +190,114 @@ __global__ __launch_bounds__(LN_THREADS) void ln_bwd_tile_kernel(int64_t M, int6
     }
 }
 
+// Backward in one pass (replicated LayerNorm).  partials[g][0][:] = dgamma, partials[g][1][:] = dbeta of the rows
+// walked by workgroup g.
+constexpr int LN_BWD_GROUPS = 256;     // workgroups of the backward kernel = rows of its partial sums
+template <typename T, int MAXC, int THREADS>
+__global__ __launch_bounds__(THREADS) void ln_bwd_fused_kernel(int64_t M, int64_t H, const T* __restrict__ dy,
+                                                                  const T* __restrict__ z,
+                                                                  const float* __restrict__ mean,
+                                                                  const float* __restrict__ rstd,
+                                                                  const T* __restrict__ gamma,
+                                                                  T* __restrict__ dz,
+                                                                  float* __restrict__ partials) {
+    __shared__ float red[THREADS / 64];
+    const int t = threadIdx.x;
+    const float inv_h = 1.0f / (float)H;
+    float gm[MAXC][8], dgam[MAXC][8], dbet[MAXC][8];
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int64_t col = ((int64_t)t + THREADS * i) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { gm[i][e] = 0.0f; dgam[i][e] = 0.0f; dbet[i][e] = 0.0f; }
+        if (col < H) load8(gamma + col, gm[i]);
+    }
+    float g[MAXC][8], zz[MAXC][8], gn[MAXC][8], zn[MAXC][8];
+    auto fetch = [&](int64_t row, float (&a)[MAXC][8], float (&b)[MAXC][8]) {
+#pragma unroll
+        for (int i = 0; i < MAXC; ++i) {
+            const int64_t col = ((int64_t)t + THREADS * i) * 8;
+            if (col < H && row < M) { load8(dy + row * H + col, a[i]); load8(z + row * H + col, b[i]); }
+        }
+    };
+    fetch(blockIdx.x, g, zz);
+    for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+        fetch(row + gridDim.x, gn, zn);                      // next row of this workgroup, in flight during the sums
+        const float mu = mean[row], rs = rstd[row];
+        float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < MAXC; ++i) {
+            const int64_t col = ((int64_t)t + THREADS * i) * 8;
+            if (col < H) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    zz[i][e] = (zz[i][e] - mu) * rs;          // zh
+                    const float gg = g[i][e] * gm[i][e];
+                    s1 += gg;
+                    s2 = fmaf(gg, zz[i][e], s2);
+                }
+            }
+        }
+        const float c1 = block_sum<THREADS / 64>(s1, red) * inv_h;
+        const float c2 = block_sum<THREADS / 64>(s2, red) * inv_h;
+#pragma unroll
+        for (int i = 0; i < MAXC; ++i) {
+            const int64_t col = ((int64_t)t + THREADS * i) * 8;
+            if (col < H) {
+                float o[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    dbet[i][e] += g[i][e];
+                    dgam[i][e] = fmaf(g[i][e], zz[i][e], dgam[i][e]);
+                    o[e] = (g[i][e] * gm[i][e] - c1 - zz[i][e] * c2) * rs;
+                }
+                store8(dz + row * H + col, o);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < MAXC; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { g[i][e] = gn[i][e]; zz[i][e] = zn[i][e]; }
+    }
+    float* pg = partials + (int64_t)blockIdx.x * 2 * H;
+#pragma unroll
+    for (int i = 0; i < MAXC; ++i) {
+        const int64_t col = ((int64_t)t + THREADS * i) * 8;
+        if (col < H) { store8(pg + col, dgam[i]); store8(pg + H + col, dbet[i]); }
+    }
+}
+
+// dgamma, dbeta = sums of the per-workgroup partials [groups][2][H], in group order within four interleaved lanes
+// that are then combined in lane order (fixed order).  64 columns x 4 group lanes per workgroup; blockIdx.y picks
+// gamma or beta.
+template <typename T>
+__global__ __launch_bounds__(256) void ln_sum_partials_kernel(int64_t groups, int64_t H, const float* __restrict__ part,
+                                                             T* __restrict__ dgamma, T* __restrict__ dbeta) {
+    __shared__ float red[4][64];
+    const int cl = threadIdx.x & 63, gl = threadIdx.x >> 6;
+    const int64_t col = (int64_t)blockIdx.x * 64 + cl;
+    const float* src = part + (int64_t)blockIdx.y * H + col;
+    float s = 0.0f;
+    if (col < H) {
+        int64_t g = gl;
+        for (; g + 12 < groups; g += 16) {           // four independent loads in flight per thread
+            const float a = src[g * 2 * H], b = src[(g + 4) * 2 * H], c = src[(g + 8) * 2 * H], d = src[(g + 12) * 2 * H];
+            s += a; s += b; s += c; s += d;
+        }
+        for (; g < groups; g += 4) s += src[g * 2 * H];
+    }
+    red[gl][cl] = s;
+    __syncthreads();
+    if (gl == 0 && col < H) {
+        const float v = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
+        (blockIdx.y == 0 ? dgamma : dbeta)[col] = from_f32<T>(v);
+    }
+}
+
 bool ln_supported(int64_t H) { return H > 0 && H % 8 == 0 && H <= 8 * 8 * LN_THREADS; }
 int64_t ln_partial_rows(int64_t M) { return (M + LN_SLAB - 1) / LN_SLAB; }
-size_t ln_scratch_bytes(int64_t M, int64_t H) {
-    return ((size_t)2 * M + (size_t)ln_partial_rows(M) * 2 * H) * sizeof(float);
-}
+static int64_t ln_bwd_groups(int64_t M) { return M < LN_BWD_GROUPS ? M : LN_BWD_GROUPS; }
+size_t ln_scratch_bytes(int64_t M, int64_t H) { return (size_t)ln_bwd_groups(M) * 2 * H * sizeof(float); }
 
 template <typename T, int MAXC>
 static hipError_t fwd_t(const LnArgs& a) {
@@ -197,23 +307,24 @@ static hipError_t fwd_t(const LnArgs& a) {
                        (T*)a.y, a.mean, a.rstd);
     return hipGetLastError();
 }
+// MAXC counts the 8-element chunks per thread of a 256-thread workgroup; rows of more than two such chunks go to
+// 512-thread workgroups with half the chunks, so that two wavefronts share each SIMD.
 template <typename T, int MAXC>
 static hipError_t bwd_t(const LnArgs& a) {
-    float* c12 = a.partials;                       // [M][2], then the column partials
-    float* part = a.partials + 2 * a.M;
-    const unsigned grid = (unsigned)(a.M < 65535 * 16 ? a.M : 65535 * 16);
-    hipLaunchKernelGGL((ln_bwd_rowstat_kernel<T, MAXC>), dim3(grid), dim3(LN_THREADS), 0, a.stream, a.M, a.H,
-                       (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma, 1.0f / (float)a.H, c12);
-    const int64_t slabs = ln_partial_rows(a.M);
-    hipLaunchKernelGGL((ln_bwd_tile_kernel<T>), dim3((unsigned)((a.H + 511) / 512), (unsigned)slabs),
-                       dim3(LN_THREADS), 0, a.stream, a.M, a.H, (const T*)a.dy, (const T*)a.z, a.mean, a.rstd,
-                       (const T*)a.gamma, c12, 1.0f, (const T*)nullptr, (T*)a.dz, part);
+    float* part = a.partials;                      // [groups][2][H]
+    const int64_t groups = ln_bwd_groups(a.M);
+    if constexpr (MAXC > 2)
+        hipLaunchKernelGGL((ln_bwd_fused_kernel<T, MAXC / 2, 512>), dim3((unsigned)groups), dim3(512), 0, a.stream, a.M,
+                           a.H, (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma, (T*)a.dz, part);
+    else
+        hipLaunchKernelGGL((ln_bwd_fused_kernel<T, MAXC, LN_THREADS>), dim3((unsigned)groups), dim3(LN_THREADS), 0,
+                           a.stream, a.M, a.H, (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma,
+                           (T*)a.dz, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // partial rows are [slab][2][H]: gamma and beta gradients are separate buffers, so two strided sums
-    e = sum_partials_strided(a.dtype, slabs, a.H, part, 2 * a.H, a.dgamma, a.stream);
-    if (e != hipSuccess) return e;
-    return sum_partials_strided(a.dtype, slabs, a.H, part + a.H, 2 * a.H, a.dbeta, a.stream);
+    hipLaunchKernelGGL((ln_sum_partials_kernel<T>), dim3((unsigned)((a.H + 63) / 64), 2), dim3(256), 0, a.stream, groups,
+                       a.H, part, (T*)a.dgamma, (T*)a.dbeta);
+    return hipGetLastError();
 }
 
 template <typename T>
@@ -221,6 +332,7 @@ static hipError_t dispatch(const LnArgs& a, bool bwd) {
     const int64_t chunks = (a.H / 8 + LN_THREADS - 1) / LN_THREADS;
     if (chunks <= 2) return bwd ? bwd_t<T, 2>(a) : fwd_t<T, 2>(a);
     if (chunks <= 4) return bwd ? bwd_t<T, 4>(a) : fwd_t<T, 4>(a);
+    if (chunks <= 6) return bwd ? bwd_t<T, 6>(a) : fwd_t<T, 6>(a);
     return bwd ? bwd_t<T, 8>(a) : fwd_t<T, 8>(a);
 }
 
