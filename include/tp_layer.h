@@ -242,13 +242,22 @@ int tp_layer_gemm(int dtype, int trans_a, int trans_b, int64_t M, int64_t N, int
                   void* ws, size_t ws_bytes, void* hip_stream);
 
 /* Softmax attention over local heads, exposed for per-kernel tests and timing.
- * qkv [B*S, 3*nl*dh] (columns q|k|v, head, dh) -> o [B*S, nl*dh], lse [B, nl, S] float. */
+ * qkv [B*S, 3*nl*dh] (columns q|k|v, head, dh) -> o [B*S, nl*dh], lse [B, nl, S] float.
+ * ws (device, 16-byte aligned, caller-owned, contents undefined afterwards) may be NULL.  With a
+ * workspace of tp_layer_attn_workspace_bytes(..., bwd) bytes the bf16 kernels may cut the tile steps
+ * of a (128-row block, head) into chunks that run as separate workgroups and are combined in chunk
+ * order by a second kernel (float partials in ws): the causal mask makes those strips triangular
+ * and the longest one would otherwise set the duration of the launch.  Results are deterministic
+ * either way; they differ between the two ways by float rounding only.  A non-NULL ws that is too
+ * small gives TPL_EWORKSPACE.  TPL_ATTN_CHUNK=<n> in the environment forces chunks of n 64-row tile
+ * steps (0: never cut); it must not change between the size query and the call. */
+size_t tp_layer_attn_workspace_bytes(int dtype, int B, int S, int nl, int dh, int causal, int bwd);
 int tp_layer_attn_fwd(int dtype, int B, int S, int nl, int dh, int causal,
-                      const void* qkv, void* o, float* lse, void* hip_stream);
+                      const void* qkv, void* o, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
 /* d_scratch: [B, nl, S] float scratch (row sums of dO*O); dqkv [B*S, 3*nl*dh]. */
 int tp_layer_attn_bwd(int dtype, int B, int S, int nl, int dh, int causal,
                       const void* qkv, const void* o, const float* lse, const void* d_o,
-                      void* dqkv, float* d_scratch, void* hip_stream);
+                      void* dqkv, float* d_scratch, void* ws, size_t ws_bytes, void* hip_stream);
 
 /* Diagnostics for benchmarks (not thread-safe, off by default).  tp_layer_profile(1) makes every
  * GEMM launched by this library (inside tp_layer_fwd / tp_layer_bwd / tp_layer_gemm) be bracketed by

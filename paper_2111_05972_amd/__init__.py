@@ -10,7 +10,7 @@ from .binding import (  # noqa: F401
     library_path, load_library, make_desc,
     tp_layer_validate, tp_layer_saved_bytes, tp_layer_saved_offsets, tp_layer_workspace_bytes,
     tp_layer_fwd, tp_layer_bwd, tp_layer_gemm, tp_layer_gemm_workspace_bytes,
-    tp_layer_attn_fwd, tp_layer_attn_bwd, tp_layer_strerror, tp_layer_profile, tp_layer_profile_read,
+    tp_layer_attn_workspace_bytes, tp_layer_attn_fwd, tp_layer_attn_bwd, tp_layer_strerror, tp_layer_profile, tp_layer_profile_read,
     tp_layer_workspace_bytes_recompute, tp_layer_bwd_recompute,
     tp_layer_ln_workspace_bytes, tp_layer_ln_fwd, tp_layer_ln_bwd,
     tp_layer_ln_moments, tp_layer_ln_stats, tp_layer_ln_apply_fwd, tp_layer_ln_apply_bwd_sums,

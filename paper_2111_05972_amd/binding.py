@@ -71,8 +71,9 @@ def load_library():
         "tp_layer_bwd": (ci, [D, P, _vp, _vp, _vp, _vp, _vp, G, _vp, _vp, _vp, sz, _vp]),
         "tp_layer_gemm_workspace_bytes": (sz, [ci, i64, i64, i64]),
         "tp_layer_gemm": (ci, [ci, ci, ci, i64, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp, ci, _vp, sz, _vp]),
-        "tp_layer_attn_fwd": (ci, [ci, ci, ci, ci, ci, ci, _vp, _vp, _vp, _vp]),
-        "tp_layer_attn_bwd": (ci, [ci, ci, ci, ci, ci, ci, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+        "tp_layer_attn_workspace_bytes": (sz, [ci, ci, ci, ci, ci, ci, ci]),
+        "tp_layer_attn_fwd": (ci, [ci, ci, ci, ci, ci, ci, _vp, _vp, _vp, _vp, sz, _vp]),
+        "tp_layer_attn_bwd": (ci, [ci, ci, ci, ci, ci, ci, _vp, _vp, _vp, _vp, _vp, _vp, _vp, sz, _vp]),
         "tp_layer_workspace_bytes_recompute": (sz, [D]),
         "tp_layer_bwd_recompute": (ci, [D, P, _vp, _vp, _vp, _vp, G, _vp, _vp, _vp, sz, _vp]),
         "tp_layer_ln_workspace_bytes": (sz, [i64, i64]),
@@ -308,19 +309,25 @@ def tp_layer_gemm(dtype, trans_a, trans_b, M, N, K, A, B, C, bias=None, resid=No
     return rc
 
 
-def tp_layer_attn_fwd(dtype, B, S, nl, dh, causal, qkv, o, lse, stream=None, check=True):
+def tp_layer_attn_workspace_bytes(dtype, B, S, nl, dh, causal, bwd):
+    return load_library().tp_layer_attn_workspace_bytes(dtype, B, S, nl, dh, int(bool(causal)), int(bool(bwd)))
+
+
+def tp_layer_attn_fwd(dtype, B, S, nl, dh, causal, qkv, o, lse, ws=None, ws_bytes=None, stream=None,
+                      check=True):
     rc = load_library().tp_layer_attn_fwd(dtype, B, S, nl, dh, int(bool(causal)), _ptr(qkv), _ptr(o),
-                                          _ptr(lse), _stream(stream))
+                                          _ptr(lse), _ptr(ws),
+                                          (_nbytes(ws) or 0) if ws_bytes is None else ws_bytes, _stream(stream))
     if check and rc != TPL_OK:
         raise TpLayerError(rc, "tp_layer_attn_fwd")
     return rc
 
 
-def tp_layer_attn_bwd(dtype, B, S, nl, dh, causal, qkv, o, lse, d_o, dqkv, d_scratch, stream=None,
-                      check=True):
+def tp_layer_attn_bwd(dtype, B, S, nl, dh, causal, qkv, o, lse, d_o, dqkv, d_scratch, ws=None,
+                      ws_bytes=None, stream=None, check=True):
     rc = load_library().tp_layer_attn_bwd(dtype, B, S, nl, dh, int(bool(causal)), _ptr(qkv), _ptr(o),
-                                          _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(d_scratch),
-                                          _stream(stream))
+                                          _ptr(lse), _ptr(d_o), _ptr(dqkv), _ptr(d_scratch), _ptr(ws),
+                                          (_nbytes(ws) or 0) if ws_bytes is None else ws_bytes, _stream(stream))
     if check and rc != TPL_OK:
         raise TpLayerError(rc, "tp_layer_attn_bwd")
     return rc

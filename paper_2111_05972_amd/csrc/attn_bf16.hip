@@ -16,7 +16,16 @@
 //
 // Backward is two kernels (dK/dV per key block, dQ per query block), each accumulating in registers
 // in a fixed order: no atomics, results are run-to-run identical.
+//
+// Strips and chunks.  The tile steps of one (128-row block, head) form a strip; under the causal mask
+// strips are triangular (2 to S/64 steps) and the longest one is the critical path of the launch.  When
+// the caller supplies a workspace, strips longer than a chunk length are cut into chunks of equal length,
+// each chunk is a workgroup of its own that writes float partials (forward: running max, sum and
+// unnormalised O; backward: partial dQ or dK, dV), and a second kernel combines the chunks of a strip in
+// chunk order.  Strips of one chunk write their result directly, as without a workspace.
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
 
 #include "device_math.h"
 #include "kernels.h"
@@ -35,6 +44,7 @@ constexpr int BLK = 32 * AW;       // rows (queries or keys) owned by a workgrou
 constexpr int TILE = 64;           // rows of the streamed operand staged in LDS per step
 constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LN2 = 0.69314718055994530942f;
+constexpr float RESCALE_LAG = 8.0f;  // forward: how far (log2) the row maximum may run ahead of the reference point
 
 // ---- LDS tile of TILE rows x DH bf16, 16-byte chunks XOR-swizzled by row -------------------------
 // Two kinds of read hit these tiles: 16-byte reads of 16 consecutive rows at one chunk (operand with
@@ -129,6 +139,72 @@ __device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, flo
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
+// ---- strips and chunks (host and device agree through these) --------------------------------------
+// Blocks are ranked heaviest first: query blocks from the last one down (forward, dQ), key blocks from the
+// first one up (dK/dV).  Workgroup `slot` of a head is chunk c of the block of rank r, slots numbered
+// rank-major, so that the heaviest chunks are dispatched first.
+__host__ __device__ inline int strip_block(bool kv_side, int nblk, int rank) { return kv_side ? rank : nblk - 1 - rank; }
+__host__ __device__ inline int strip_tiles(bool causal, bool kv_side, int S, int blk) {
+    const int nt = (S + TILE - 1) / TILE;
+    if (!causal) return nt;
+    if (kv_side) return nt - (blk * BLK) / TILE;          // query tiles from the diagonal to the end
+    const int end = (blk + 1) * BLK < S ? (blk + 1) * BLK : S;
+    return (end + TILE - 1) / TILE;                       // key tiles from 0 to the diagonal
+}
+// Chunk length with the multiplier that replaces the division by it (the slot search runs in every workgroup):
+// magic = floor(2^32 / ch) + 1 gives floor(n / ch) = (n * magic) >> 32 exactly for n * ch < 2^32 (here n, ch < 2^16).
+struct ChunkLen { int ch; unsigned magic; };
+inline ChunkLen make_chunk_len(int ch) {
+    return ChunkLen{ch, ch > 1 && ch < (1 << 16) ? (unsigned)((1ull << 32) / (unsigned)ch) + 1u : 0u};
+}
+__host__ __device__ inline int strip_chunks(int tiles, ChunkLen ch) {
+    if (tiles <= ch.ch) return 1;
+    if (ch.ch == 1) return tiles;
+    return (int)(((unsigned long long)(unsigned)(tiles + ch.ch - 1) * ch.magic) >> 32);
+}
+__host__ __device__ inline int strip_slots(bool causal, bool kv_side, int S, ChunkLen ch) {
+    const int nblk = (S + BLK - 1) / BLK;
+    int n = 0;
+    for (int r = 0; r < nblk; ++r) n += strip_chunks(strip_tiles(causal, kv_side, S, strip_block(kv_side, nblk, r)), ch);
+    return n;
+}
+struct Chunk {
+    int blk;        // query block (forward, dQ) or key block (dK/dV)
+    int nch;        // chunks of this block's strip
+    int slot0;      // slot of the strip's chunk 0
+    int t0, t1;     // tile steps [t0, t1) of this chunk
+};
+// Chunk of workgroup `slot`; with slot < 0: the strip of block `want_blk` (t0, t1 = whole strip).
+__device__ inline Chunk find_chunk(bool causal, bool kv_side, int S, ChunkLen ch, int slot, int want_blk) {
+    const int nblk = (S + BLK - 1) / BLK;
+    const int nt = (S + TILE - 1) / TILE;
+    Chunk k{0, 1, 0, 0, 0};
+    int acc = 0;
+    for (int r = 0; r < nblk; ++r) {
+        const int blk = strip_block(kv_side, nblk, r);
+        const int tiles = strip_tiles(causal, kv_side, S, blk);
+        const int nch = strip_chunks(tiles, ch);
+        const bool hit = slot >= 0 ? slot < acc + nch : blk == want_blk;
+        if (hit) {
+            const int first = kv_side ? nt - tiles : 0;
+            k.blk = blk; k.nch = nch; k.slot0 = acc;
+            if (slot >= 0) {
+                const int c = slot - acc, len = (tiles + nch - 1) / nch;
+                k.t0 = first + c * len;
+                k.t1 = first + ((c + 1) * len < tiles ? (c + 1) * len : tiles);
+            } else {
+                k.t0 = first; k.t1 = first + tiles;
+            }
+            return k;
+        }
+        acc += nch;
+    }
+    return k;
+}
+__device__ __forceinline__ void store_f4(float* p, float a, float b, float c, float d) {
+    *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+}
+
 // =================================================================================================
 // Forward.  Workgroup = (query block of 128, batch*head), 8 wavefronts: wavefront w owns the 32
 // queries of sub-block w % 4 and, of every 64-key tile streamed through double-buffered LDS, the key
@@ -145,17 +221,19 @@ template <int DH> constexpr int fwd_lds_bytes() {
 }
 
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(FTHREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv,
                                                             bf16_t* __restrict__ o,
-                                                            float* __restrict__ lse, int S, int nl) {
+                                                            float* __restrict__ lse, int S, int nl, int BH,
+                                                            float* __restrict__ part, ChunkLen ch) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TB = tile_bytes<DH>();
     constexpr int NCH = NCHUNKS<DH, FTHREADS>;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5;
     const int qs = wave & 3, kvh = wave >> 2;
-    const int nqb = (S + BLK - 1) / BLK;
-    const int qb = nqb - 1 - (int)blockIdx.x;            // longest (last) causal blocks first
-    const int b = blockIdx.y / nl, h = blockIdx.y % nl;
+    const int bh = blockIdx.x % BH, slot = blockIdx.x / BH;      // head fastest: heaviest chunks of all heads first
+    const Chunk ck = find_chunk(CAUSAL, false, S, ch, slot, 0);
+    const int qb = ck.blk;
+    const int b = bh / nl, h = bh % nl;
     const int64_t ld = 3LL * nl * DH;
     const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * DH;
     const bf16_t* kbase = qbase + (int64_t)nl * DH;
@@ -174,17 +252,17 @@ __global__ __launch_bounds__(FTHREADS) void attn_fwd_kernel(const bf16_t* __rest
     float m = -INFINITY, lsum = 0.0f;
 
     const int kv_end = CAUSAL ? min(S, (qb + 1) * BLK) : S;
-    const int ntiles = (kv_end + TILE - 1) / TILE;
+    const int tile0 = ck.t0, ntiles = ck.t1;
     uint4 rk[NCH], rv[NCH];
-    tile_g2r<DH, FTHREADS>(rk, kbase, ld, 0, S, t);
-    tile_g2r<DH, FTHREADS>(rv, vbase, ld, 0, S, t);
+    tile_g2r<DH, FTHREADS>(rk, kbase, ld, tile0 * TILE, S, t);
+    tile_g2r<DH, FTHREADS>(rv, vbase, ld, tile0 * TILE, S, t);
     tile_r2s<DH, FTHREADS>(smem, rk, t);
     tile_r2s<DH, FTHREADS>(smem + TB, rv, t);
     __syncthreads();
-    for (int kt = 0; kt < ntiles; ++kt) {
-        const char* ks_ = smem + (kt & 1) * 2 * TB;
+    for (int kt = tile0; kt < ntiles; ++kt) {
+        const char* ks_ = smem + ((kt - tile0) & 1) * 2 * TB;
         const char* vs_ = ks_ + TB;
-        char* nxt = smem + ((kt + 1) & 1) * 2 * TB;
+        char* nxt = smem + ((kt - tile0 + 1) & 1) * 2 * TB;
         const bool more = kt + 1 < ntiles;
         if (more) {
             tile_g2r<DH, FTHREADS>(rk, kbase, ld, (kt + 1) * TILE, S, t);
@@ -192,9 +270,22 @@ __global__ __launch_bounds__(FTHREADS) void attn_fwd_kernel(const bf16_t* __rest
         }
         const int kv0 = kt * TILE + kvh * 32;
         if (kv0 < kv_end && !(CAUSAL && kv0 > q0 + 31)) {                 // wavefront-uniform
+            // All K fragments are requested before the first MFMA and all V fragments before the softmax arithmetic,
+            // so that LDS latency is paid once per phase instead of once per MFMA (the fences keep that order).
             f32x16 s = zero16();
+            bf16x8 fr[DH / 16];
 #pragma unroll
-            for (int ks = 0; ks < DH / 16; ++ks) s = MFMA(frag_k<DH>(ks_, kvh * 32, ks, lane), qf[ks], s);
+            for (int ks = 0; ks < DH / 16; ++ks) fr[ks] = frag_k<DH>(ks_, kvh * 32, ks, lane);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < DH / 16; ++ks) s = MFMA(fr[ks], qf[ks], s);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int dt = 0; dt < DH / 32; ++dt) {
+                fr[2 * dt] = frag_t<DH>(vs_, dt * 32, kvh * 32, lane);
+                fr[2 * dt + 1] = frag_t<DH>(vs_, dt * 32, kvh * 32 + 16, lane);
+            }
+            __builtin_amdgcn_sched_barrier(0);
             // masking is needed only in tiles that straddle the diagonal or the end of the sequence
             if (kv0 + 31 >= S || (CAUSAL && kv0 + 31 > q0)) {
 #pragma unroll
@@ -208,7 +299,11 @@ __global__ __launch_bounds__(FTHREADS) void attn_fwd_kernel(const bf16_t* __rest
 #pragma unroll
             for (int v = 1; v < 16; ++v) mb = fmaxf(mb, s[v]);
             mb = fmaxf(mb, __shfl_xor(mb, 32, 64)) * c2;      // c2 > 0: scaling commutes with max
-            float mn = fmaxf(m, mb);
+            // The reference point m of the running sums moves only when the maximum has grown by more than
+            // RESCALE_LAG (log2 units): probabilities then reach 2^RESCALE_LAG at most, which float sums and
+            // bf16 operands hold without loss, and the accumulators are rescaled in a few early tiles only
+            // instead of in most of them.  Any reference point gives the same O and LSE up to rounding.
+            const float mn = (mb - m > RESCALE_LAG) ? mb : m;   // false for NaN (-inf - -inf): m stays
             float mu = mn == -INFINITY ? 0.0f : mn;
             float alpha = fast_exp2(m - mu);
             m = mn;
@@ -225,8 +320,8 @@ __global__ __launch_bounds__(FTHREADS) void attn_fwd_kernel(const bf16_t* __rest
             bf16x8 pb0 = pack_regs(s, 0), pb1 = pack_regs(s, 8);
 #pragma unroll
             for (int dt = 0; dt < DH / 32; ++dt) {
-                oacc[dt] = MFMA(frag_t<DH>(vs_, dt * 32, kvh * 32, lane), pb0, oacc[dt]);
-                oacc[dt] = MFMA(frag_t<DH>(vs_, dt * 32, kvh * 32 + 16, lane), pb1, oacc[dt]);
+                oacc[dt] = MFMA(fr[2 * dt], pb0, oacc[dt]);
+                oacc[dt] = MFMA(fr[2 * dt + 1], pb1, oacc[dt]);
             }
         }
         if (more) {
@@ -254,7 +349,22 @@ __global__ __launch_bounds__(FTHREADS) void attn_fwd_kernel(const bf16_t* __rest
         const float f0 = fast_exp2(m - mu), f1 = fast_exp2(m1 - mu);
         const float ltot = lsum * f0 + l1 * f1;
         const float inv = ltot > 0.0f ? 1.0f / ltot : 0.0f;
-        if (q < S) {
+        if (ck.nch > 1) {
+            // one chunk of a longer strip: (max, sum, unnormalised O) of this chunk's keys, float, [query][dh]
+            float* pp = part + ((int64_t)slot * BH + bh) * (BLK * (DH + 2));
+            const int ql = qs * 32 + (lane & 31);
+#pragma unroll
+            for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float r[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        r[j] = oacc[dt][4 * i + j] * f0 + mg[(2 + dt * 16 + 4 * i + j) * 64] * f1;
+                    store_f4(pp + ql * DH + dt * 32 + 8 * i + 4 * half, r[0], r[1], r[2], r[3]);
+                }
+            if (half == 0) { pp[BLK * DH + ql] = mn; pp[BLK * DH + BLK + ql] = ltot; }
+        } else if (q < S) {
             bf16_t* op = o + ((int64_t)b * S + q) * ((int64_t)nl * DH) + (int64_t)h * DH;
 #pragma unroll
             for (int dt = 0; dt < DH / 32; ++dt)
@@ -268,6 +378,73 @@ __global__ __launch_bounds__(FTHREADS) void attn_fwd_kernel(const bf16_t* __rest
                 }
             if (half == 0) lse[((int64_t)b * nl + h) * S + q] = (mn + log2f(ltot)) * LN2;
         }
+    }
+}
+
+// Forward, second kernel: merges the chunks of every strip that was cut (max, rescale, add, in chunk order),
+// normalises and writes O and LSE.  Workgroup = (256 / (DH/4) query rows of a block, batch*head); DH/4 threads per row.
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_fwd_combine_kernel(const float* __restrict__ part, bf16_t* __restrict__ o,
+                                                               float* __restrict__ lse, int S, int nl, int BH, ChunkLen ch,
+                                                               int blk0) {
+    constexpr int TPR = DH / 4, PSZ = BLK * (DH + 2), RPW = 256 / TPR, WPB = BLK / RPW;
+    const Chunk ck = find_chunk(CAUSAL, false, S, ch, -1, blk0 + (int)blockIdx.x / WPB);
+    if (ck.nch == 1) return;
+    const int bh = blockIdx.y, b = bh / nl, h = bh % nl;
+    const int tc = threadIdx.x % TPR;
+    {
+        const int ql = ((int)blockIdx.x % WPB) * RPW + threadIdx.x / TPR;
+        const int q = ck.blk * BLK + ql;
+        if (q >= S) return;
+        const float* p0 = part + ((int64_t)ck.slot0 * BH + bh) * PSZ;
+        float mtot = -INFINITY;
+        for (int c = 0; c < ck.nch; ++c) mtot = fmaxf(mtot, p0[(int64_t)c * BH * PSZ + BLK * DH + ql]);
+        const float mu = mtot == -INFINITY ? 0.0f : mtot;
+        float ltot = 0.0f, a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+        for (int c = 0; c < ck.nch; ++c) {
+            const float* pc = p0 + (int64_t)c * BH * PSZ;
+            const float f = fast_exp2(pc[BLK * DH + ql] - mu);
+            ltot = fmaf(pc[BLK * DH + BLK + ql], f, ltot);
+            const float4 v = *reinterpret_cast<const float4*>(pc + ql * DH + 4 * tc);
+            a0 = fmaf(v.x, f, a0); a1 = fmaf(v.y, f, a1); a2 = fmaf(v.z, f, a2); a3 = fmaf(v.w, f, a3);
+        }
+        const float inv = ltot > 0.0f ? 1.0f / ltot : 0.0f;
+        store4(o + ((int64_t)b * S + q) * ((int64_t)nl * DH) + (int64_t)h * DH + 4 * tc, a0 * inv, a1 * inv, a2 * inv,
+               a3 * inv);
+        if (tc == 0) lse[((int64_t)b * nl + h) * S + q] = (mtot + log2f(ltot)) * LN2;
+    }
+}
+
+// Backward, last kernel: dQ, dK, dV of every strip that was cut = sum of its chunks' partials in chunk order.
+// blockIdx.z = 0: dQ (query-block strips), 1: dK, 2: dV (key-block strips; a slot holds [dK | dV]); workgroup =
+// (256 / (DH/4) rows of a block, batch*head), DH/4 threads per row.
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_bwd_combine_kernel(const float* __restrict__ part_q,
+                                                               const float* __restrict__ part_kv,
+                                                               bf16_t* __restrict__ dqkv, int S, int nl, int BH, ChunkLen ch,
+                                                               int blk0_q, int ncut_q, int blk0_kv, int ncut_kv) {
+    constexpr int TPR = DH / 4, RPW = 256 / TPR, WPB = BLK / RPW;
+    const int which = blockIdx.z;
+    if ((int)blockIdx.x / WPB >= (which == 0 ? ncut_q : ncut_kv)) return;
+    const Chunk ck = find_chunk(CAUSAL, which != 0, S, ch, -1, (which == 0 ? blk0_q : blk0_kv) + (int)blockIdx.x / WPB);
+    if (ck.nch == 1) return;
+    const int bh = blockIdx.y, b = bh / nl, h = bh % nl;
+    const int psz = which == 0 ? BLK * DH : 2 * BLK * DH;
+    const float* p0 = (which == 0 ? part_q : part_kv) + ((int64_t)ck.slot0 * BH + bh) * psz + (which == 2 ? BLK * DH : 0);
+    const float f = which == 2 ? 1.0f : 1.0f / sqrtf((float)DH);
+    const int64_t ld = 3LL * nl * DH;
+    const int tc = threadIdx.x % TPR;
+    {
+        const int rl = ((int)blockIdx.x % WPB) * RPW + threadIdx.x / TPR;
+        const int row = ck.blk * BLK + rl;
+        if (row >= S) return;
+        float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+        for (int c = 0; c < ck.nch; ++c) {
+            const float4 v = *reinterpret_cast<const float4*>(p0 + (int64_t)c * BH * psz + rl * DH + 4 * tc);
+            a0 += v.x; a1 += v.y; a2 += v.z; a3 += v.w;
+        }
+        store4(dqkv + ((int64_t)b * S + row) * ld + (int64_t)which * nl * DH + (int64_t)h * DH + 4 * tc, a0 * f, a1 * f,
+               a2 * f, a3 * f);
     }
 }
 
@@ -311,13 +488,13 @@ template <int DH, bool CAUSAL, bool DK_ROLE>
 __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restrict__ qkv,
                                               const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
                                               const float* __restrict__ dsum, bf16_t* __restrict__ dqkv,
-                                              int S, int nl) {
+                                              int S, int nl, int bh, const Chunk& ck, float* __restrict__ pslot) {
     constexpr int TB = tile_bytes<DH>();
     constexpr int NCH = NCHUNKS<DH, FTHREADS>;
     constexpr int STAGE = 2 * TB + 2 * TILE * 4;          // Q tile, dO tile, LSE*log2e, D
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5;
-    const int kb = blockIdx.x;
-    const int b = blockIdx.y / nl, h = blockIdx.y % nl;
+    const int kb = ck.blk;
+    const int b = bh / nl, h = bh % nl;
     const int64_t ld = 3LL * nl * DH, ldo = (int64_t)nl * DH;
     const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * DH;
     const bf16_t* kbase = qbase + (int64_t)nl * DH;
@@ -340,8 +517,7 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
 #pragma unroll
     for (int dt = 0; dt < DH / 32; ++dt) acc[dt] = zero16();
 
-    const int qt0 = CAUSAL ? (kb * BLK) / TILE : 0;       // first query tile that can see this key block
-    const int ntiles = (S + TILE - 1) / TILE;
+    const int qt0 = ck.t0, ntiles = ck.t1;                // query tiles of this chunk (the strip starts at the diagonal)
     uint4 rq[NCH], rdo[NCH];
     float rl = 0.0f, rd = 0.0f;
     auto g2r = [&](int qt) {
@@ -376,13 +552,37 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
         for (int sb = 0; sb < 2; ++sb) {
             const int qs0 = qt * TILE + sb * 32;
             if (qs0 >= S || (CAUSAL && qs0 + 31 < k0)) continue;          // wavefront-uniform
+            // Fragments of all MFMA phases (Q for S, dO for dP in the dK role, then Q or dO transposed) through a
+            // rolling window of W registers, as in the dQ kernel.
             f32x16 s = zero16(), dp = zero16();
+            constexpr int NF = DH / 16, W = DH == 64 ? NF : NF / 2, NP = DK_ROLE ? 2 * NF : NF;
+            bf16x8 fr[W];
+            const char* src = DK_ROLE ? qs : dos;                          // dK += dS^T Q ; dV += P^T dO
+            auto fetch = [&](int i) {
+                if (i < NF) return frag_k<DH>(qs, sb * 32, i, lane);
+                if (i < NP) return frag_k<DH>(dos, sb * 32, i - NF, lane);
+                const int k = i - NP;
+                return frag_t<DH>(src, (k >> 1) * 32, sb * 32 + (k & 1) * 16, lane);
+            };
 #pragma unroll
-            for (int ks = 0; ks < DH / 16; ++ks) {
-                s = MFMA(frag_k<DH>(qs, sb * 32, ks, lane), kf[ks], s);
-                if (DK_ROLE) dp = MFMA(frag_k<DH>(dos, sb * 32, ks, lane), vf[ks], dp);
+            for (int i = 0; i < W; ++i) fr[i] = fetch(i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                if (i < NF) s = MFMA(fr[i % W], kf[i], s);
+                else dp = MFMA(fr[i % W], vf[DK_ROLE ? i - NF : 0], dp);
+                fr[i % W] = fetch(i + W);
+                __builtin_amdgcn_sched_barrier(0);
             }
             const bool need_mask = qs0 + 31 >= S || k0 + 31 >= S || (CAUSAL && k0 + 31 > qs0);
+            if (need_mask) {                          // wave-uniform: only tiles on the diagonal or at the end of S
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    int qi = qs0 + 8 * (v >> 2) + 4 * half + (v & 3);
+                    bool ok = qi < S && kv < S && (!CAUSAL || kv <= qi);
+                    s[v] = ok ? s[v] : -INFINITY;         // exp2(-inf) = 0
+                }
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float4 l4 = *reinterpret_cast<const float4*>(ls + sb * 32 + 8 * i + 4 * half);
@@ -392,27 +592,33 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     int v = 4 * i + j;
-                    float p = fast_exp2(fmaf(s[v], c2, -lv[j]));
-                    if (need_mask) {
-                        int qi = qs0 + 8 * i + 4 * half + j;
-                        bool ok = qi < S && kv < S && (!CAUSAL || kv <= qi);
-                        p = ok ? p : 0.0f;
-                    }
+                    const float p = fast_exp2(fmaf(s[v], c2, -lv[j]));
                     s[v] = DK_ROLE ? p * (dp[v] - dvv[j]) : p;             // dS, or P
                 }
             }
             bf16x8 g0 = pack_regs(s, 0), g1 = pack_regs(s, 8);
-            const char* src = DK_ROLE ? qs : dos;                          // dK += dS^T Q ; dV += P^T dO
 #pragma unroll
-            for (int dt = 0; dt < DH / 32; ++dt) {
-                acc[dt] = MFMA(frag_t<DH>(src, dt * 32, sb * 32, lane), g0, acc[dt]);
-                acc[dt] = MFMA(frag_t<DH>(src, dt * 32, sb * 32 + 16, lane), g1, acc[dt]);
+            for (int k = 0; k < NF; ++k) {
+                acc[k >> 1] = MFMA(fr[k % W], (k & 1) ? g1 : g0, acc[k >> 1]);
+                if (k + W < NF) {
+                    fr[k % W] = fetch(NP + k + W);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
         if (more) r2s(nxt);
         __syncthreads();
     }
-    if (kv < S) {
+    if (ck.nch > 1) {
+        // one chunk of a longer strip: unscaled float partial, [dK | dV][key][dh]
+        float* pp = pslot + (DK_ROLE ? 0 : BLK * DH) + ((wave & 3) * 32 + (lane & 31)) * DH;
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                store_f4(pp + dt * 32 + 8 * i + 4 * half, acc[dt][4 * i], acc[dt][4 * i + 1], acc[dt][4 * i + 2],
+                         acc[dt][4 * i + 3]);
+    } else if (kv < S) {
         bf16_t* outp = dqkv + ((int64_t)b * S + kv) * ld + (int64_t)(DK_ROLE ? 1 : 2) * nl * DH + (int64_t)h * DH;
         const float f = DK_ROLE ? scale : 1.0f;
 #pragma unroll
@@ -425,15 +631,19 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
 }
 
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(FTHREADS) void attn_dkv_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(FTHREADS, 2) void attn_dkv_kernel(const bf16_t* __restrict__ qkv,
                                                             const bf16_t* __restrict__ d_o,
                                                             const float* __restrict__ lse,
                                                             const float* __restrict__ dsum,
-                                                            bf16_t* __restrict__ dqkv, int S, int nl) {
+                                                            bf16_t* __restrict__ dqkv, int S, int nl, int BH,
+                                                            float* __restrict__ part, ChunkLen ch) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int bh = blockIdx.x % BH, slot = blockIdx.x / BH;
+    const Chunk ck = find_chunk(CAUSAL, true, S, ch, slot, 0);
+    float* pslot = part + ((int64_t)slot * BH + bh) * (2 * BLK * DH);
     // the role is uniform per wavefront; both bodies run the same loop and the same barriers
-    if ((threadIdx.x >> 6) < 4) attn_dkv_body<DH, CAUSAL, false>(smem, qkv, d_o, lse, dsum, dqkv, S, nl);
-    else attn_dkv_body<DH, CAUSAL, true>(smem, qkv, d_o, lse, dsum, dqkv, S, nl);
+    if ((threadIdx.x >> 6) < 4) attn_dkv_body<DH, CAUSAL, false>(smem, qkv, d_o, lse, dsum, dqkv, S, nl, bh, ck, pslot);
+    else attn_dkv_body<DH, CAUSAL, true>(smem, qkv, d_o, lse, dsum, dqkv, S, nl, bh, ck, pslot);
 }
 
 // =================================================================================================
@@ -448,19 +658,21 @@ template <int DH> constexpr int dq_lds_bytes() {
 }
 
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(FTHREADS) void attn_dq_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __restrict__ qkv,
                                                            const bf16_t* __restrict__ d_o,
                                                            const float* __restrict__ lse,
                                                            const float* __restrict__ dsum,
-                                                           bf16_t* __restrict__ dqkv, int S, int nl) {
+                                                           bf16_t* __restrict__ dqkv, int S, int nl, int BH,
+                                                           float* __restrict__ part, ChunkLen ch) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int TB = tile_bytes<DH>();
     constexpr int NCH = NCHUNKS<DH, FTHREADS>;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5;
     const int qs = wave & 3, kvh = wave >> 2;
-    const int nqb = (S + BLK - 1) / BLK;
-    const int qb = nqb - 1 - (int)blockIdx.x;
-    const int b = blockIdx.y / nl, h = blockIdx.y % nl;
+    const int bh = blockIdx.x % BH, slot = blockIdx.x / BH;
+    const Chunk ck = find_chunk(CAUSAL, false, S, ch, slot, 0);
+    const int qb = ck.blk;
+    const int b = bh / nl, h = bh % nl;
     const int64_t ld = 3LL * nl * DH, ldo = (int64_t)nl * DH;
     const bf16_t* qbase = qkv + (int64_t)b * S * ld + (int64_t)h * DH;
     const bf16_t* kbase = qbase + (int64_t)nl * DH;
@@ -484,17 +696,17 @@ __global__ __launch_bounds__(FTHREADS) void attn_dq_kernel(const bf16_t* __restr
     for (int dt = 0; dt < DH / 32; ++dt) dq[dt] = zero16();
 
     const int kv_end = CAUSAL ? min(S, (qb + 1) * BLK) : S;
-    const int ntiles = (kv_end + TILE - 1) / TILE;
+    const int tile0 = ck.t0, ntiles = ck.t1;
     uint4 rk[NCH], rv[NCH];
-    tile_g2r<DH, FTHREADS>(rk, kbase, ld, 0, S, t);
-    tile_g2r<DH, FTHREADS>(rv, vbase, ld, 0, S, t);
+    tile_g2r<DH, FTHREADS>(rk, kbase, ld, tile0 * TILE, S, t);
+    tile_g2r<DH, FTHREADS>(rv, vbase, ld, tile0 * TILE, S, t);
     tile_r2s<DH, FTHREADS>(smem, rk, t);
     tile_r2s<DH, FTHREADS>(smem + TB, rv, t);
     __syncthreads();
-    for (int kt = 0; kt < ntiles; ++kt) {
-        const char* ks_ = smem + (kt & 1) * 2 * TB;
+    for (int kt = tile0; kt < ntiles; ++kt) {
+        const char* ks_ = smem + ((kt - tile0) & 1) * 2 * TB;
         const char* vs_ = ks_ + TB;
-        char* nxt = smem + ((kt + 1) & 1) * 2 * TB;
+        char* nxt = smem + ((kt - tile0 + 1) & 1) * 2 * TB;
         const bool more = kt + 1 < ntiles;
         if (more) {
             tile_g2r<DH, FTHREADS>(rk, kbase, ld, (kt + 1) * TILE, S, t);
@@ -502,28 +714,47 @@ __global__ __launch_bounds__(FTHREADS) void attn_dq_kernel(const bf16_t* __restr
         }
         const int kv0 = kt * TILE + kvh * 32;
         if (kv0 < kv_end && !(CAUSAL && kv0 > q0 + 31)) {                 // wavefront-uniform
+            // The fragments of the three MFMA phases (K for S, V for dP, K transposed for dQ) form one sequence that
+            // is read through a rolling window of W registers: fragment i + W is requested right after the MFMA
+            // that used fragment i, so LDS latency hides under W MFMAs instead of being paid before every one.
             f32x16 s = zero16(), dp = zero16();
+            constexpr int NF = DH / 16, W = DH == 64 ? NF : NF / 2;
+            bf16x8 fr[W];
+            auto fetch = [&](int i) {                       // i is a compile-time constant after unrolling
+                if (i < NF) return frag_k<DH>(ks_, kvh * 32, i, lane);
+                if (i < 2 * NF) return frag_k<DH>(vs_, kvh * 32, i - NF, lane);
+                const int k = i - 2 * NF;
+                return frag_t<DH>(ks_, (k >> 1) * 32, kvh * 32 + (k & 1) * 16, lane);
+            };
 #pragma unroll
-            for (int ks = 0; ks < DH / 16; ++ks) {
-                s = MFMA(frag_k<DH>(ks_, kvh * 32, ks, lane), qf[ks], s);
-                dp = MFMA(frag_k<DH>(vs_, kvh * 32, ks, lane), dof[ks], dp);
+            for (int i = 0; i < W; ++i) fr[i] = fetch(i);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 2 * NF; ++i) {
+                if (i < NF) s = MFMA(fr[i % W], qf[i], s);
+                else dp = MFMA(fr[i % W], dof[i - NF], dp);
+                fr[i % W] = fetch(i + W);
+                __builtin_amdgcn_sched_barrier(0);
             }
             const bool need_mask = q0 + 31 >= S || kv0 + 31 >= S || (CAUSAL && kv0 + 31 > q0);
+            if (need_mask) {                          // wave-uniform: only tiles on the diagonal or at the end of S
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float p = fast_exp2(fmaf(s[v], c2, -l2));
-                if (need_mask) {
+                for (int v = 0; v < 16; ++v) {
                     int kv = kv0 + (v >> 2) * 8 + half * 4 + (v & 3);
                     bool ok = q < S && kv < S && (!CAUSAL || kv <= q);
-                    p = ok ? p : 0.0f;
+                    s[v] = ok ? s[v] : -INFINITY;         // exp2(-inf) = 0
                 }
-                dp[v] = p * (dp[v] - dq_d);
             }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) dp[v] = fast_exp2(fmaf(s[v], c2, -l2)) * (dp[v] - dq_d);
             bf16x8 g0 = pack_regs(dp, 0), g1 = pack_regs(dp, 8);
 #pragma unroll
-            for (int dt = 0; dt < DH / 32; ++dt) {
-                dq[dt] = MFMA(frag_t<DH>(ks_, dt * 32, kvh * 32, lane), g0, dq[dt]);
-                dq[dt] = MFMA(frag_t<DH>(ks_, dt * 32, kvh * 32 + 16, lane), g1, dq[dt]);
+            for (int k = 0; k < NF; ++k) {
+                dq[k >> 1] = MFMA(fr[k % W], (k & 1) ? g1 : g0, dq[k >> 1]);
+                if (k + W < NF) {
+                    fr[k % W] = fetch(2 * NF + k + W);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
         if (more) {
@@ -540,7 +771,19 @@ __global__ __launch_bounds__(FTHREADS) void attn_dq_kernel(const bf16_t* __restr
             for (int v = 0; v < 16; ++v) mg[(dt * 16 + v) * 64] = dq[dt][v];
     }
     __syncthreads();
-    if (kvh == 0 && q < S) {
+    if (kvh == 0 && ck.nch > 1) {
+        // one chunk of a longer strip: unscaled float partial, [query][dh]
+        float* pp = part + ((int64_t)slot * BH + bh) * (BLK * DH) + (qs * 32 + (lane & 31)) * DH;
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float r[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) r[j] = dq[dt][4 * i + j] + mg[(dt * 16 + 4 * i + j) * 64];
+                store_f4(pp + dt * 32 + 8 * i + 4 * half, r[0], r[1], r[2], r[3]);
+            }
+    } else if (kvh == 0 && q < S) {
         bf16_t* dqp = dqkv + ((int64_t)b * S + q) * ld + (int64_t)h * DH;
 #pragma unroll
         for (int dt = 0; dt < DH / 32; ++dt)
@@ -565,6 +808,65 @@ static hipError_t set_lds(K kernel, int bytes) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
+// Chunk length in tile steps.  No workspace: strips are never cut.  TPL_ATTN_CHUNK=<n> forces n (0: never cut).
+// Otherwise strips are cut only when there are fewer strips than compute units (with more, the units that finish
+// their short strips early pick up the queued ones, and cutting only adds the cost of the partials): the shortest
+// chunk length of at least 4 steps for which the chunks of all heads still run in one round (one workgroup per
+// compute unit, 5 % over allowed).  Every workgroup costs a few steps' worth of start-up and merge, so more and
+// shorter chunks than that measured slower.
+static int chunk_tiles(const AttnArgs& a, bool bwd) {
+    constexpr int NEVER = 1 << 30;
+    (void)bwd;
+    if (!a.ws) return NEVER;
+    if (const char* e = getenv("TPL_ATTN_CHUNK")) {
+        const int v = atoi(e);
+        return v > 0 && v < (1 << 16) ? v : NEVER;
+    }
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0;
+        hipDeviceProp_t pr;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&pr, dev) != hipSuccess) return NEVER;
+        cus = pr.multiProcessorCount;
+    }
+    const int64_t bh = (int64_t)a.B * a.nl, nblk = (a.S + BLK - 1) / BLK;
+    if (nblk * bh >= cus) return NEVER;
+    const int longest = (a.S + TILE - 1) / TILE;
+    for (int ch = 4; ch < longest; ++ch)
+        if (strip_slots(a.causal, false, a.S, make_chunk_len(ch)) * bh * 100 <= 105LL * cus) return ch;
+    return NEVER;
+}
+static size_t part_bytes_fwd(const AttnArgs& a, ChunkLen ch) {
+    return (size_t)strip_slots(a.causal, false, a.S, ch) * a.B * a.nl * BLK * (a.dh + 2) * sizeof(float);
+}
+static size_t part_bytes_dq(const AttnArgs& a, ChunkLen ch) {
+    return (size_t)strip_slots(a.causal, false, a.S, ch) * a.B * a.nl * BLK * a.dh * sizeof(float);
+}
+static size_t part_bytes_dkv(const AttnArgs& a, ChunkLen ch) {
+    return (size_t)strip_slots(a.causal, true, a.S, ch) * a.B * a.nl * BLK * 2 * a.dh * sizeof(float);
+}
+// Blocks whose strips are cut: a contiguous range (strip length is monotonic in the block index).
+static void cut_range(const AttnArgs& a, bool kv_side, ChunkLen ch, int* blk0, int* n) {
+    const int nblk = (a.S + BLK - 1) / BLK;
+    int lo = nblk, hi = -1;
+    for (int blk = 0; blk < nblk; ++blk)
+        if (strip_tiles(a.causal, kv_side, a.S, blk) > ch.ch) { lo = blk < lo ? blk : lo; hi = blk; }
+    *blk0 = hi < 0 ? 0 : lo;
+    *n = hi < 0 ? 0 : hi - lo + 1;
+}
+static bool cuts(const AttnArgs& a, bool kv_side, ChunkLen ch) {
+    return strip_slots(a.causal, kv_side, a.S, ch) != (a.S + BLK - 1) / BLK;
+}
+// Workspace that lets the strips be cut (0: they would not be cut anyway).  Sized with a stand-in non-null
+// workspace pointer so that the same rule decides as at launch.
+size_t attn_bf16_workspace_bytes(const AttnArgs& a0, bool bwd) {
+    AttnArgs a = a0;
+    a.ws = reinterpret_cast<void*>(16);
+    const ChunkLen ch = make_chunk_len(chunk_tiles(a, bwd));
+    if (!bwd) return cuts(a, false, ch) ? part_bytes_fwd(a, ch) : 0;
+    return (cuts(a, false, ch) ? part_bytes_dq(a, ch) : 0) + (cuts(a, true, ch) ? part_bytes_dkv(a, ch) : 0);
+}
+
 template <int DH, bool CAUSAL>
 static hipError_t fwd_t(const AttnArgs& a) {
     constexpr int LDS = fwd_lds_bytes<DH>();
@@ -574,9 +876,19 @@ static hipError_t fwd_t(const AttnArgs& a) {
         if (e != hipSuccess) return e;
         once = true;
     }
-    dim3 grid((a.S + BLK - 1) / BLK, a.B * a.nl);
-    hipLaunchKernelGGL((attn_fwd_kernel<DH, CAUSAL>), grid, dim3(FTHREADS), LDS, a.stream,
-                       (const bf16_t*)a.qkv, (bf16_t*)a.o, a.lse, a.S, a.nl);
+    const ChunkLen ch = make_chunk_len(chunk_tiles(a, false));
+    if (a.ws && cuts(a, false, ch) && part_bytes_fwd(a, ch) > a.ws_bytes) return hipErrorInvalidValue;
+    const int BH = a.B * a.nl;
+    const int64_t wgs = (int64_t)strip_slots(CAUSAL, false, a.S, ch) * BH;
+    if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+    float* part = static_cast<float*>(a.ws);
+    hipLaunchKernelGGL((attn_fwd_kernel<DH, CAUSAL>), dim3((unsigned)wgs), dim3(FTHREADS), LDS, a.stream,
+                       (const bf16_t*)a.qkv, (bf16_t*)a.o, a.lse, a.S, a.nl, BH, part, ch);
+    int blk0 = 0, ncut = 0;
+    cut_range(a, false, ch, &blk0, &ncut);
+    if (ncut)
+        hipLaunchKernelGGL((attn_fwd_combine_kernel<DH, CAUSAL>), dim3(ncut * (BLK * DH / 1024), BH), dim3(256), 0,
+                           a.stream, part, (bf16_t*)a.o, a.lse, a.S, a.nl, BH, ch, blk0);
     return hipGetLastError();
 }
 
@@ -592,14 +904,32 @@ static hipError_t bwd_t(const AttnArgs& a) {
         if (e != hipSuccess) return e;
         once = true;
     }
+    const ChunkLen ch = make_chunk_len(chunk_tiles(a, true));
+    const bool cut_q = cuts(a, false, ch), cut_kv = cuts(a, true, ch);
+    const size_t bytes_q = cut_q ? part_bytes_dq(a, ch) : 0, bytes_kv = cut_kv ? part_bytes_dkv(a, ch) : 0;
+    if (a.ws && bytes_q + bytes_kv > a.ws_bytes) return hipErrorInvalidValue;
+    const int BH = a.B * a.nl;
+    const int64_t wgs_q = (int64_t)strip_slots(CAUSAL, false, a.S, ch) * BH;
+    const int64_t wgs_kv = (int64_t)strip_slots(CAUSAL, true, a.S, ch) * BH;
+    if (wgs_q > 0x7fffffffLL || wgs_kv > 0x7fffffffLL) return hipErrorInvalidValue;
+    float* part_q = static_cast<float*>(a.ws);
+    float* part_kv = a.ws ? reinterpret_cast<float*>(static_cast<char*>(a.ws) + bytes_q) : nullptr;
     const int64_t rows = (int64_t)a.B * a.S;
     hipLaunchKernelGGL((attn_dsum_kernel<DH>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, a.stream,
                        (const bf16_t*)a.o, (const bf16_t*)a.d_o, a.dsum, a.B, a.S, a.nl);
-    dim3 grid((a.S + BLK - 1) / BLK, a.B * a.nl);
-    hipLaunchKernelGGL((attn_dkv_kernel<DH, CAUSAL>), grid, dim3(FTHREADS), LDS_KV, a.stream,
-                       (const bf16_t*)a.qkv, (const bf16_t*)a.d_o, a.lse, a.dsum, (bf16_t*)a.dqkv, a.S, a.nl);
-    hipLaunchKernelGGL((attn_dq_kernel<DH, CAUSAL>), grid, dim3(FTHREADS), LDS_Q, a.stream,
-                       (const bf16_t*)a.qkv, (const bf16_t*)a.d_o, a.lse, a.dsum, (bf16_t*)a.dqkv, a.S, a.nl);
+    hipLaunchKernelGGL((attn_dkv_kernel<DH, CAUSAL>), dim3((unsigned)wgs_kv), dim3(FTHREADS), LDS_KV, a.stream,
+                       (const bf16_t*)a.qkv, (const bf16_t*)a.d_o, a.lse, a.dsum, (bf16_t*)a.dqkv, a.S, a.nl, BH,
+                       part_kv, ch);
+    hipLaunchKernelGGL((attn_dq_kernel<DH, CAUSAL>), dim3((unsigned)wgs_q), dim3(FTHREADS), LDS_Q, a.stream,
+                       (const bf16_t*)a.qkv, (const bf16_t*)a.d_o, a.lse, a.dsum, (bf16_t*)a.dqkv, a.S, a.nl, BH,
+                       part_q, ch);
+    int blk0_q = 0, ncut_q = 0, blk0_kv = 0, ncut_kv = 0;
+    cut_range(a, false, ch, &blk0_q, &ncut_q);
+    cut_range(a, true, ch, &blk0_kv, &ncut_kv);
+    if (ncut_q || ncut_kv)
+        hipLaunchKernelGGL((attn_bwd_combine_kernel<DH, CAUSAL>),
+                           dim3((ncut_q > ncut_kv ? ncut_q : ncut_kv) * (BLK * DH / 1024), BH, 3), dim3(256), 0, a.stream,
+                           part_q, part_kv, (bf16_t*)a.dqkv, a.S, a.nl, BH, ch, blk0_q, ncut_q, blk0_kv, ncut_kv);
     return hipGetLastError();
 }
 

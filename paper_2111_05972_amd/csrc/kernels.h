@@ -36,6 +36,8 @@ struct AttnArgs {
     const void* d_o;   // bwd only
     void* dqkv;        // bwd only
     float* dsum;       // bwd only: [B, nl, S] scratch, rowsum(dO * O)
+    void* ws;          // optional (bf16 kernels): float partials that let long strips be cut into chunks
+    size_t ws_bytes;
     hipStream_t stream;
 };
 
@@ -95,5 +97,6 @@ hipError_t gemm_bf16(const GemmArgs& a);
 bool attn_bf16_supported(const AttnArgs& a);
 hipError_t attn_bf16_fwd(const AttnArgs& a);
 hipError_t attn_bf16_bwd(const AttnArgs& a);
+size_t attn_bf16_workspace_bytes(const AttnArgs& a, bool bwd);
 
 }  // namespace tpl

@@ -65,7 +65,15 @@ size_t gemm_ws(int dtype, int64_t M, int64_t N, int64_t K) {
 }
 
 // Backward scratch: dU, dO, dQKV, D, and per chain (attention, MLP) column-sum partials and GEMM scratch.
-struct BwdWs { size_t du, d_o, dqkv, dsum, colsum, colsum2, gemm, gemm2, gemm_each, total; };
+struct BwdWs { size_t du, d_o, dqkv, dsum, colsum, colsum2, gemm, gemm2, gemm_each, attn, attn_bytes, total; };
+
+// Float partials that let the attention kernels cut long strips into chunks (0 when they would not).
+size_t attn_ws(const Dims& x, bool bwd) {
+    AttnArgs a{};
+    a.dtype = x.dtype; a.B = (int)x.B; a.S = (int)x.S; a.nl = (int)x.nl; a.dh = (int)x.dh; a.causal = x.causal;
+    if (x.dtype != BF16 || !attn_bf16_supported(a)) return 0;
+    return up(attn_bf16_workspace_bytes(a, bwd));
+}
 
 size_t fwd_gemm_ws(const Dims& x) {
     size_t g = 0;
@@ -75,6 +83,7 @@ size_t fwd_gemm_ws(const Dims& x) {
     g = std::max(g, gemm_ws(x.dtype, x.M, x.H, x.Il));
     return std::max(g, ALIGN);
 }
+size_t fwd_ws_total(const Dims& x) { return 2 * fwd_gemm_ws(x) + attn_ws(x, false); }
 
 void bwd_layout(const Dims& x, BwdWs* W) {
     size_t off = 0;
@@ -95,6 +104,8 @@ void bwd_layout(const Dims& x, BwdWs* W) {
     W->gemm_each = g;
     W->gemm = off; off += g;
     W->gemm2 = off; off += g;
+    W->attn_bytes = attn_ws(x, true);
+    W->attn = off; off += W->attn_bytes;
     W->total = off;
 }
 
@@ -220,6 +231,8 @@ int fwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
     AttnArgs at{};
     at.dtype = x.dtype; at.B = (int)x.B; at.S = (int)x.S; at.nl = (int)x.nl; at.dh = (int)x.dh;
     at.causal = x.causal; at.qkv = qkv; at.o = o; at.lse = lse; at.stream = s;
+    at.ws_bytes = attn_ws(x, false);
+    at.ws = at.ws_bytes ? (char*)ws + 2 * half : nullptr;
     if ((rc = run_attn(at, false))) return rc;
     if (row_parallel) {
         GemmArgs g3 = mk(x, 0, 0, x.M, x.H, x.Hl, o, p->w_o, y_attn, sc);
@@ -255,7 +268,7 @@ int tp_layer_saved_offsets(const tp_layer_desc* desc, tp_layer_saved_layout* out
 size_t tp_layer_workspace_bytes(const tp_layer_desc* desc, int bwd) {
     Dims x;
     if (resolve(desc, &x) != TPL_OK) return 0;
-    if (!bwd) return 2 * fwd_gemm_ws(x);
+    if (!bwd) return fwd_ws_total(x);
     BwdWs W;
     bwd_layout(x, &W);
     return W.total;
@@ -332,6 +345,8 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     at.dtype = x.dtype; at.B = (int)x.B; at.S = (int)x.S; at.nl = (int)x.nl; at.dh = (int)x.dh;
     at.causal = x.causal; at.qkv = qkv; at.o = const_cast<void*>(o); at.lse = const_cast<float*>(lse);
     at.d_o = d_o; at.dqkv = dqkv; at.dsum = dsum; at.stream = s;
+    at.ws_bytes = W.attn_bytes;
+    at.ws = W.attn_bytes ? w + W.attn : nullptr;
     if ((rc = run_attn(at, true))) return rc;
     GemmArgs w1 = mk(x, 1, 0, x.H, 3 * x.Hl, x.M, x_attn, dqkv, gr->dw_qkv, sc);
     if ((rc = run_gemm(w1))) return rc;
@@ -349,7 +364,7 @@ size_t tp_layer_workspace_bytes_recompute(const tp_layer_desc* desc) {
     saved_layout(x, &L);
     BwdWs W;
     bwd_layout(x, &W);
-    return up(L.total) + W.total;
+    return up(L.total) + std::max(W.total, fwd_ws_total(x));
 }
 
 int tp_layer_bwd_recompute(const tp_layer_desc* desc, const tp_layer_params* p, const void* x_attn,
@@ -555,30 +570,40 @@ static int attn_check(int dtype, int B, int S, int nl, int dh) {
     return TPL_OK;
 }
 
+size_t tp_layer_attn_workspace_bytes(int dtype, int B, int S, int nl, int dh, int causal, int bwd) {
+    if (attn_check(dtype, B, S, nl, dh)) return 0;
+    AttnArgs a{};
+    a.dtype = dtype; a.B = B; a.S = S; a.nl = nl; a.dh = dh; a.causal = causal != 0;
+    if (dtype != BF16 || !attn_bf16_supported(a)) return 0;
+    return up(attn_bf16_workspace_bytes(a, bwd != 0));
+}
+
 int tp_layer_attn_fwd(int dtype, int B, int S, int nl, int dh, int causal, const void* qkv, void* o,
-                      float* lse, void* hip_stream) {
+                      float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
     int rc = attn_check(dtype, B, S, nl, dh);
     if (rc) return rc;
     if (!qkv || !o || !lse) return TPL_EINVAL;
-    if (misaligned(qkv) || misaligned(o) || misaligned(lse)) return TPL_EALIGN;
+    if (misaligned(qkv) || misaligned(o) || misaligned(lse) || misaligned(ws)) return TPL_EALIGN;
+    if (ws && ws_bytes < tp_layer_attn_workspace_bytes(dtype, B, S, nl, dh, causal, 0)) return TPL_EWORKSPACE;
     AttnArgs a{};
     a.dtype = dtype; a.B = B; a.S = S; a.nl = nl; a.dh = dh; a.causal = causal != 0;
-    a.qkv = qkv; a.o = o; a.lse = lse; a.stream = (hipStream_t)hip_stream;
+    a.qkv = qkv; a.o = o; a.lse = lse; a.ws = ws; a.ws_bytes = ws_bytes; a.stream = (hipStream_t)hip_stream;
     return run_attn(a, false);
 }
 
 int tp_layer_attn_bwd(int dtype, int B, int S, int nl, int dh, int causal, const void* qkv,
                       const void* o, const float* lse, const void* d_o, void* dqkv,
-                      float* d_scratch, void* hip_stream) {
+                      float* d_scratch, void* ws, size_t ws_bytes, void* hip_stream) {
     int rc = attn_check(dtype, B, S, nl, dh);
     if (rc) return rc;
     if (!qkv || !o || !lse || !d_o || !dqkv || !d_scratch) return TPL_EINVAL;
-    const void* ptrs[] = {qkv, o, lse, d_o, dqkv, d_scratch};
+    const void* ptrs[] = {qkv, o, lse, d_o, dqkv, d_scratch, ws};
     for (const void* pp : ptrs) if (misaligned(pp)) return TPL_EALIGN;
+    if (ws && ws_bytes < tp_layer_attn_workspace_bytes(dtype, B, S, nl, dh, causal, 1)) return TPL_EWORKSPACE;
     AttnArgs a{};
     a.dtype = dtype; a.B = B; a.S = S; a.nl = nl; a.dh = dh; a.causal = causal != 0;
     a.qkv = qkv; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse); a.d_o = d_o;
-    a.dqkv = dqkv; a.dsum = d_scratch; a.stream = (hipStream_t)hip_stream;
+    a.dqkv = dqkv; a.dsum = d_scratch; a.ws = ws; a.ws_bytes = ws_bytes; a.stream = (hipStream_t)hip_stream;
     return run_attn(a, true);
 }
 

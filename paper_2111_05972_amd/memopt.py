@@ -64,7 +64,9 @@ class MemOptRank:
                        (M, Hl, H), (Hl, H, M), (M, Hs, 3 * H), (Hs, 3 * H, M)]
         nws = max(B.tp_layer_ln_apply_workspace_bytes(M, Hs),
                   B.tp_layer_slice_epilogue_workspace_bytes(M, max(3 * Hl, Il, Hs)),
-                  max(B.tp_layer_gemm_workspace_bytes(dtype, *g) for g in gemm_shapes), 256)
+                  max(B.tp_layer_gemm_workspace_bytes(dtype, *g) for g in gemm_shapes),
+                  max(B.tp_layer_attn_workspace_bytes(dtype, self.B, self.S, self.nl, self.dh, self.causal, bwd)
+                      for bwd in (False, True)), 256)
         self.ws = torch.empty(nws, dtype=torch.uint8, device=device)
         self.grads = {k: e(*s) for k, s in PARAM_SHAPES(H, self.Hs, self.Hl, I, self.Il).items()}
 
@@ -98,7 +100,7 @@ class MemOptRank:
         B.tp_layer_slice_epilogue_fwd(self.dtype, B.TPL_ACT_NONE, self.M, 3 * self.Hl, qkv_in, self.p["b_qkv"], None,
                                       None, self.qkv, stream=st)
         B.tp_layer_attn_fwd(self.dtype, self.B, self.S, self.nl, self.dh, self.causal, self.qkv, self.o, self.lse,
-                            stream=st)
+                            ws=self.ws, stream=st)
         out = self._part(self.H)
         self._gemm(0, 0, self.M, self.H, self.Hl, self.o, self.p["w_o"], out)
         return out
@@ -166,7 +168,7 @@ class MemOptRank:
         self._gemm(0, 1, self.M, self.Hl, self.H, dy1_full, self.p["w_o"], self.d_o)
         self._gemm(1, 0, self.Hl, self.H, self.M, self.o, dy1_full, self.grads["w_o"])
         B.tp_layer_attn_bwd(self.dtype, self.B, self.S, self.nl, self.dh, self.causal, self.qkv, self.o, self.lse,
-                            self.d_o, self.dqkv, self.dsum, stream=st)
+                            self.d_o, self.dqkv, self.dsum, ws=self.ws, stream=st)
         B.tp_layer_slice_epilogue_bwd(self.dtype, B.TPL_ACT_NONE, self.M, 3 * self.Hl, self.dqkv, None, None,
                                       self.grads["b_qkv"], self.ws, stream=st)
         return self.dqkv

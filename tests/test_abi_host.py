@@ -110,6 +110,25 @@ def test_calls_are_rejected_before_any_launch():
     assert "workspace" in pkg.tp_layer_strerror(pkg.TPL_EWORKSPACE)
 
 
+def test_attention_workspace_follows_the_chunk_length(monkeypatch):
+    """Partials of the cut strips: causal S = 300 has query strips of 2, 4, 5 tile steps and key strips of 5, 3, 1;
+    with chunks of 2 steps that is 1 + 2 + 3 slots on the query side and 3 + 2 + 1 on the key side."""
+    import paper_2111_05972_amd as pkg
+    B, S, nl, dh = 2, 300, 3, 128
+    monkeypatch.setenv("TPL_ATTN_CHUNK", "2")
+    up = lambda n: (n + 255) // 256 * 256      # noqa: E731
+    assert pkg.tp_layer_attn_workspace_bytes(pkg.TPL_BF16, B, S, nl, dh, 1, 0) == up(6 * B * nl * 128 * (dh + 2) * 4)
+    assert pkg.tp_layer_attn_workspace_bytes(pkg.TPL_BF16, B, S, nl, dh, 1, 1) == up(6 * B * nl * 128 * 3 * dh * 4)
+    assert pkg.tp_layer_attn_workspace_bytes(pkg.TPL_F32, B, S, nl, dh, 1, 0) == 0
+    ok = 4096
+    assert pkg.tp_layer_attn_fwd(pkg.TPL_BF16, B, S, nl, dh, 1, ok, ok, ok, ws=ok, ws_bytes=1024,
+                                 check=False) == pkg.TPL_EWORKSPACE
+    assert pkg.tp_layer_attn_bwd(pkg.TPL_BF16, B, S, nl, dh, 1, ok, ok, ok, ok, ok, ok, ws=ok, ws_bytes=1024,
+                                 check=False) == pkg.TPL_EWORKSPACE
+    monkeypatch.setenv("TPL_ATTN_CHUNK", "0")
+    assert pkg.tp_layer_attn_workspace_bytes(pkg.TPL_BF16, B, S, nl, dh, 1, 1) == 0
+
+
 def test_package_sharding_helper_matches_oracle_rule():
     import numpy as np
     import oracle

@@ -108,15 +108,28 @@ def test_gemm_k_shares_own_choice(ta, tb, monkeypatch):
 ATTN_CASES = [(2, 128, 2, 64), (1, 300, 3, 128), (3, 77, 2, 32), (1, 1, 4, 64), (2, 513, 1, 64), (1, 1024, 2, 128)]
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+# chunk: None = no workspace (strips never cut); "auto" = workspace, the library's own chunk length;
+# "1", "3" = workspace and chunks of that many 64-row tile steps (every strip longer than that is cut).
+@pytest.mark.parametrize("dtype,chunk", [("bf16", None), ("bf16", "auto"), ("bf16", "1"), ("bf16", "3"), ("f32", None)])
 @pytest.mark.parametrize("causal", [True, False])
-def test_attention_fwd_bwd(dtype, causal):
+def test_attention_fwd_bwd(dtype, chunk, causal, monkeypatch):
     import torch
     import paper_2111_05972_amd as pkg
     dt = pkg.TPL_BF16 if dtype == "bf16" else pkg.TPL_F32
     tol = 2e-2 if dtype == "bf16" else 1e-4
+    monkeypatch.delenv("TPL_ATTN_CHUNK", raising=False)
+    if chunk not in (None, "auto"):
+        monkeypatch.setenv("TPL_ATTN_CHUNK", chunk)
     for ci, (B, S, nl, dh) in enumerate(ATTN_CASES):
-        print(f"\n[attn] {dtype} causal={causal} B={B} S={S} nl={nl} dh={dh}", flush=True)
+        print(f"\n[attn] {dtype} causal={causal} chunk={chunk} B={B} S={S} nl={nl} dh={dh}", flush=True)
+        ws_f = ws_b = None
+        if chunk is not None:
+            nf, nb = (pkg.tp_layer_attn_workspace_bytes(dt, B, S, nl, dh, causal, bwd) for bwd in (False, True))
+            if chunk == "1" and S > 64 and dh in (64, 128):
+                assert nf > 0 and nb > 0                       # these strips are cut
+            # filled with NaN: a partial that is read without having been written shows up
+            ws_f = torch.full((max(nf, 16) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+            ws_b = torch.full((max(nb, 16) // 4,), float("nan"), dtype=torch.float32, device="cuda")
         qkv = _draw(700 + ci, (B * S, 3 * nl * dh), 1.0, dtype)
         d_o = _draw(800 + ci, (B * S, nl * dh), 1.0, dtype)
         t = qkv.reshape(B, S, 3, nl, dh).astype(np.float64)
@@ -127,7 +140,7 @@ def test_attention_fwd_bwd(dtype, causal):
         o_d = torch.empty(B * S, nl * dh, dtype=qkv_d.dtype, device="cuda")
         lse_d = torch.empty(B, nl, S, dtype=torch.float32, device="cuda")
         st = torch.cuda.current_stream()
-        pkg.tp_layer_attn_fwd(dt, B, S, nl, dh, causal, qkv_d, o_d, lse_d, stream=st)
+        pkg.tp_layer_attn_fwd(dt, B, S, nl, dh, causal, qkv_d, o_d, lse_d, ws=ws_f, stream=st)
         torch.cuda.synchronize()
         assert oracle.max_rel_err(o_d.float().cpu().numpy(), o_ref) <= tol
         assert np.abs(lse_d.cpu().numpy() - LSE).max() <= (2e-2 if dtype == "bf16" else 1e-4)
@@ -137,7 +150,8 @@ def test_attention_fwd_bwd(dtype, causal):
         ref = np.stack([a.transpose(0, 2, 1, 3) for a in (dQ, dK, dV)], axis=2).reshape(B * S, 3 * nl * dh)
         dqkv_d = torch.empty_like(qkv_d)
         scratch = torch.empty(B, nl, S, dtype=torch.float32, device="cuda")
-        pkg.tp_layer_attn_bwd(dt, B, S, nl, dh, causal, qkv_d, o_d, lse_d, _t(d_o, dt), dqkv_d, scratch, stream=st)
+        pkg.tp_layer_attn_bwd(dt, B, S, nl, dh, causal, qkv_d, o_d, lse_d, _t(d_o, dt), dqkv_d, scratch, ws=ws_b,
+                              stream=st)
         torch.cuda.synchronize()
         got = dqkv_d.float().cpu().numpy()
         for i, nm in enumerate(("dQ", "dK", "dV")):

@@ -71,6 +71,21 @@ def test_flag_on_variant_of_headline_shape_small_seq():
     _run(small_variant(C[5], name="gpt3-175b-tp8-epi", seq=256, row_epilogue=True))
 
 
+@pytest.mark.parametrize("chunk", ["1", "2"])
+def test_attention_strips_cut_into_chunks(chunk, monkeypatch):
+    """The layer with its attention strips cut into chunks of 1 or 2 tile steps (partials in the workspace,
+    combined by a second kernel), and the same twice over: bit-identical."""
+    monkeypatch.setenv("TPL_ATTN_CHUNK", chunk)
+    cfg = small_variant(C[2], name="bf16-dh128-causal-chunks", hidden=1024, heads=8, head_dim=128,
+                        intermediate=2048, tp_degree=4, tp_rank=2, seq=333, micro_batch=2, causal=True,
+                        row_epilogue=True)
+    _run(cfg)
+    d, sh = shard_inputs(cfg)
+    a, b = gpu_outputs(cfg, d, sh, repeat=2)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+
+
 def test_run_to_run_determinism():
     cfg = SMALL[3]
     d, sh = shard_inputs(cfg)
