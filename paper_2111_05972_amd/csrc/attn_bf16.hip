@@ -29,6 +29,7 @@
 
 #include "device_math.h"
 #include "kernels.h"
+#include "lds_dma.h"
 
 namespace tpl {
 
@@ -60,30 +61,41 @@ template <int DH> constexpr int tile_bytes() { return TILE * DH * 2; }
 template <int DH, int NT> constexpr int NCHUNKS = TILE * DH / 8 / NT;     // 16-byte chunks per thread and tile
 template <int DH> constexpr int chunks_per_thread() { return NCHUNKS<DH, ATHREADS>; }
 
-// global -> registers; rows >= nrows read as zero.  base points at row 0, column 0 of the head.
-template <int DH, int NT = ATHREADS>
-__device__ __forceinline__ void tile_g2r(uint4 (&r)[(NCHUNKS<DH, NT>)], const bf16_t* base,
-                                         int64_t ld, int row0, int nrows, int t) {
+// ---- global -> LDS without passing through registers ---------------------------------------------
+// A tile is TILE rows x DH bf16 = TILE*DH/8 chunks of 16 bytes; a buffer load with the LDS flag writes the 64
+// chunks of a wavefront to 64 consecutive LDS positions.  Position p = t + NT*i (row p / NC, slot p % NC) must
+// hold chunk (slot ^ swz(row)) of its row, so the swizzle is applied to the global offset each lane requests.
+// Offsets are relative to row 0 of this (batch, head); the descriptor ends after the head's slice of row S-1,
+// which makes rows >= S read as zero.
+template <int DH, int NT>
+__device__ __forceinline__ void dma_offsets(unsigned (&off)[(NCHUNKS<DH, NT>)], int64_t ld, int t) {
     constexpr int NC = DH / 8;
 #pragma unroll
     for (int i = 0; i < NCHUNKS<DH, NT>; ++i) {
-        int q = t + NT * i;
-        int row = q / NC, c = q % NC;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (row0 + row < nrows) v = *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + row) * ld + c * 8);
-        r[i] = v;
+        const int p = t + NT * i, row = p / NC, c = (p % NC) ^ swz<DH>(row);
+        off[i] = (unsigned)row * (unsigned)(ld * 2) + (unsigned)c * 16u;
     }
 }
-template <int DH, int NT = ATHREADS>
-__device__ __forceinline__ void tile_r2s(char* tile, const uint4 (&r)[(NCHUNKS<DH, NT>)], int t) {
-    constexpr int NC = DH / 8;
+template <int DH>
+__device__ __forceinline__ i32x4 head_rsrc(const bf16_t* base, int64_t ld, int S) {
+    return make_rsrc(base, (unsigned)(((int64_t)(S - 1) * ld + DH) * 2));
+}
+// rows [row0, row0 + TILE) -> LDS tile at byte address lds_tile; wave = wavefront index (uniform)
+template <int DH, int NT>
+__device__ __forceinline__ void tile_dma(i32x4 rsrc, unsigned lds_tile, const unsigned (&off)[(NCHUNKS<DH, NT>)],
+                                         unsigned row0_bytes, int wave) {
 #pragma unroll
-    for (int i = 0; i < NCHUNKS<DH, NT>; ++i) {
-        int q = t + NT * i;
-        int row = q / NC, c = q % NC;
-        *reinterpret_cast<uint4*>(tile + row * (DH * 2) + ((c ^ swz<DH>(row)) << 4)) = r[i];
-    }
+    for (int i = 0; i < NCHUNKS<DH, NT>; ++i)
+        buffer_load_lds_b128(rsrc, lds_tile + (unsigned)(i * NT + wave * 64) * 16u, off[i] + row0_bytes);
 }
+// A use of v that the compiler must order after the load that produces v: placed before a streaming loop, it
+// makes the compiler wait for prologue loads there, instead of inside the loop at their first use, where the
+// wait (a count of all loads in flight) would also drain the tile requested for the next step.
+template <typename T> __device__ __forceinline__ void settle(const T& v) { asm volatile("" ::"v"(v)); }
+// The loads above are invisible to the compiler's own wait counting: wait for all of them before the barrier
+// that hands the tile to the readers.
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // MFMA operand with the head dimension as K: row (row_base + lane%32), dh = 16*ks + 8*(lane/32) + 0..7
 template <int DH>
 __device__ __forceinline__ bf16x8 frag_k(const char* tile, int row_base, int ks, int lane) {
@@ -253,21 +265,26 @@ __global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(co
 
     const int kv_end = CAUSAL ? min(S, (qb + 1) * BLK) : S;
     const int tile0 = ck.t0, ntiles = ck.t1;
-    uint4 rk[NCH], rv[NCH];
-    tile_g2r<DH, FTHREADS>(rk, kbase, ld, tile0 * TILE, S, t);
-    tile_g2r<DH, FTHREADS>(rv, vbase, ld, tile0 * TILE, S, t);
-    tile_r2s<DH, FTHREADS>(smem, rk, t);
-    tile_r2s<DH, FTHREADS>(smem + TB, rv, t);
+    const unsigned lds0 = (unsigned)(uintptr_t)(lds_void_ptr)smem;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const i32x4 desc_k = head_rsrc<DH>(kbase, ld, S), desc_v = head_rsrc<DH>(vbase, ld, S);
+    unsigned off[NCH];
+    dma_offsets<DH, FTHREADS>(off, ld, t);
+    auto fetch_tile = [&](int kt, unsigned stage) {       // K and V rows of tile kt -> LDS stage
+        const unsigned r0 = (unsigned)kt * TILE * (unsigned)(ld * 2);
+        tile_dma<DH, FTHREADS>(desc_k, stage, off, r0, wave_u);
+        tile_dma<DH, FTHREADS>(desc_v, stage + TB, off, r0, wave_u);
+    };
+    fetch_tile(tile0, lds0);
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) settle(qf[ks]);
+    dma_wait();
     __syncthreads();
     for (int kt = tile0; kt < ntiles; ++kt) {
         const char* ks_ = smem + ((kt - tile0) & 1) * 2 * TB;
         const char* vs_ = ks_ + TB;
-        char* nxt = smem + ((kt - tile0 + 1) & 1) * 2 * TB;
-        const bool more = kt + 1 < ntiles;
-        if (more) {
-            tile_g2r<DH, FTHREADS>(rk, kbase, ld, (kt + 1) * TILE, S, t);
-            tile_g2r<DH, FTHREADS>(rv, vbase, ld, (kt + 1) * TILE, S, t);
-        }
+        // the other stage was last read before the barrier that ended the previous step
+        if (kt + 1 < ntiles) fetch_tile(kt + 1, lds0 + ((kt - tile0 + 1) & 1) * 2 * TB);
         const int kv0 = kt * TILE + kvh * 32;
         if (kv0 < kv_end && !(CAUSAL && kv0 > q0 + 31)) {                 // wavefront-uniform
             // All K fragments are requested before the first MFMA and all V fragments before the softmax arithmetic,
@@ -324,10 +341,7 @@ __global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(co
                 oacc[dt] = MFMA(fr[2 * dt + 1], pb1, oacc[dt]);
             }
         }
-        if (more) {
-            tile_r2s<DH, FTHREADS>(nxt, rk, t);
-            tile_r2s<DH, FTHREADS>(nxt + TB, rv, t);
-        }
+        dma_wait();
         __syncthreads();
     }
     lsum += __shfl_xor(lsum, 32, 64);
@@ -518,11 +532,17 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
     for (int dt = 0; dt < DH / 32; ++dt) acc[dt] = zero16();
 
     const int qt0 = ck.t0, ntiles = ck.t1;                // query tiles of this chunk (the strip starts at the diagonal)
-    uint4 rq[NCH], rdo[NCH];
+    const unsigned lds0 = (unsigned)(uintptr_t)(lds_void_ptr)smem;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const i32x4 desc_q = head_rsrc<DH>(qbase, ld, S), desc_do = head_rsrc<DH>(dobase, ldo, S);
+    unsigned off_q[NCH], off_do[NCH];
+    dma_offsets<DH, FTHREADS>(off_q, ld, t);
+    dma_offsets<DH, FTHREADS>(off_do, ldo, t);
     float rl = 0.0f, rd = 0.0f;
-    auto g2r = [&](int qt) {
-        tile_g2r<DH, FTHREADS>(rq, qbase, ld, qt * TILE, S, t);
-        tile_g2r<DH, FTHREADS>(rdo, dobase, ldo, qt * TILE, S, t);
+    // Q and dO rows of tile qt straight into LDS; LSE and D of its rows through registers (r2s stores them)
+    auto g2r = [&](int qt, unsigned stage) {
+        tile_dma<DH, FTHREADS>(desc_q, stage, off_q, (unsigned)qt * TILE * (unsigned)(ld * 2), wave_u);
+        tile_dma<DH, FTHREADS>(desc_do, stage + TB, off_do, (unsigned)qt * TILE * (unsigned)(ldo * 2), wave_u);
         if (t < TILE) {
             int qi = qt * TILE + t;
             rl = qi < S ? lrow[qi] * LOG2E : 0.0f;
@@ -530,14 +550,18 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
         }
     };
     auto r2s = [&](char* st) {
-        tile_r2s<DH, FTHREADS>(st, rq, t);
-        tile_r2s<DH, FTHREADS>(st + TB, rdo, t);
         if (t < TILE) {
             reinterpret_cast<float*>(st + 2 * TB)[t] = rl;
             reinterpret_cast<float*>(st + 2 * TB)[TILE + t] = rd;
         }
     };
-    if (qt0 < ntiles) { g2r(qt0); r2s(smem); }
+    if (qt0 < ntiles) { g2r(qt0, lds0); r2s(smem); }
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) {
+        settle(kf[ks]);
+        if (DK_ROLE) settle(vf[ks]);
+    }
+    dma_wait();
     __syncthreads();
     for (int qt = qt0; qt < ntiles; ++qt) {
         const char* st = smem + ((qt - qt0) & 1) * STAGE;
@@ -547,7 +571,7 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
         const float* ls = reinterpret_cast<const float*>(st + 2 * TB);
         const float* ds_ = ls + TILE;
         const bool more = qt + 1 < ntiles;
-        if (more) g2r(qt + 1);
+        if (more) g2r(qt + 1, lds0 + ((qt - qt0 + 1) & 1) * STAGE);
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
             const int qs0 = qt * TILE + sb * 32;
@@ -607,6 +631,7 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
             }
         }
         if (more) r2s(nxt);
+        dma_wait();
         __syncthreads();
     }
     if (ck.nch > 1) {
@@ -697,21 +722,28 @@ __global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __re
 
     const int kv_end = CAUSAL ? min(S, (qb + 1) * BLK) : S;
     const int tile0 = ck.t0, ntiles = ck.t1;
-    uint4 rk[NCH], rv[NCH];
-    tile_g2r<DH, FTHREADS>(rk, kbase, ld, tile0 * TILE, S, t);
-    tile_g2r<DH, FTHREADS>(rv, vbase, ld, tile0 * TILE, S, t);
-    tile_r2s<DH, FTHREADS>(smem, rk, t);
-    tile_r2s<DH, FTHREADS>(smem + TB, rv, t);
+    const unsigned lds0 = (unsigned)(uintptr_t)(lds_void_ptr)smem;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const i32x4 desc_k = head_rsrc<DH>(kbase, ld, S), desc_v = head_rsrc<DH>(vbase, ld, S);
+    unsigned off[NCH];
+    dma_offsets<DH, FTHREADS>(off, ld, t);
+    auto fetch_tile = [&](int kt, unsigned stage) {       // K and V rows of tile kt -> LDS stage
+        const unsigned r0 = (unsigned)kt * TILE * (unsigned)(ld * 2);
+        tile_dma<DH, FTHREADS>(desc_k, stage, off, r0, wave_u);
+        tile_dma<DH, FTHREADS>(desc_v, stage + TB, off, r0, wave_u);
+    };
+    fetch_tile(tile0, lds0);
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) { settle(qf[ks]); settle(dof[ks]); }
+    settle(l2);
+    settle(dq_d);
+    dma_wait();
     __syncthreads();
     for (int kt = tile0; kt < ntiles; ++kt) {
         const char* ks_ = smem + ((kt - tile0) & 1) * 2 * TB;
         const char* vs_ = ks_ + TB;
-        char* nxt = smem + ((kt - tile0 + 1) & 1) * 2 * TB;
-        const bool more = kt + 1 < ntiles;
-        if (more) {
-            tile_g2r<DH, FTHREADS>(rk, kbase, ld, (kt + 1) * TILE, S, t);
-            tile_g2r<DH, FTHREADS>(rv, vbase, ld, (kt + 1) * TILE, S, t);
-        }
+        // the other stage was last read before the barrier that ended the previous step
+        if (kt + 1 < ntiles) fetch_tile(kt + 1, lds0 + ((kt - tile0 + 1) & 1) * 2 * TB);
         const int kv0 = kt * TILE + kvh * 32;
         if (kv0 < kv_end && !(CAUSAL && kv0 > q0 + 31)) {                 // wavefront-uniform
             // The fragments of the three MFMA phases (K for S, V for dP, K transposed for dQ) form one sequence that
@@ -757,10 +789,7 @@ __global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __re
                 }
             }
         }
-        if (more) {
-            tile_r2s<DH, FTHREADS>(nxt, rk, t);
-            tile_r2s<DH, FTHREADS>(nxt + TB, rv, t);
-        }
+        dma_wait();
         __syncthreads();
     }
     float* mg = reinterpret_cast<float*>(smem) + (qs * (DH / 2)) * 64 + lane;   // element i at mg[i * 64]
@@ -799,7 +828,9 @@ __global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __re
 
 // ---- host side ----------------------------------------------------------------------------------
 bool attn_bf16_supported(const AttnArgs& a) {
-    return a.dtype == BF16 && (a.dh == 64 || a.dh == 128) && a.S >= 1 && (int64_t)a.B * a.nl <= 65535;
+    // tile loads address a (batch, head) slice with 32-bit byte offsets
+    return a.dtype == BF16 && (a.dh == 64 || a.dh == 128) && a.S >= 1 && (int64_t)a.B * a.nl <= 65535 &&
+           (int64_t)a.S * 3 * a.nl * a.dh * 2 < (1LL << 31);
 }
 
 template <typename K>
@@ -811,7 +842,7 @@ static hipError_t set_lds(K kernel, int bytes) {
 // Chunk length in tile steps.  No workspace: strips are never cut.  TPL_ATTN_CHUNK=<n> forces n (0: never cut).
 // Otherwise strips are cut only when there are fewer strips than compute units (with more, the units that finish
 // their short strips early pick up the queued ones, and cutting only adds the cost of the partials): the shortest
-// chunk length of at least 4 steps for which the chunks of all heads still run in one round (one workgroup per
+// chunk length of at least 8 steps for which the chunks of all heads still run in one round (one workgroup per
 // compute unit, 5 % over allowed).  Every workgroup costs a few steps' worth of start-up and merge, so more and
 // shorter chunks than that measured slower.
 static int chunk_tiles(const AttnArgs& a, bool bwd) {
@@ -832,7 +863,7 @@ static int chunk_tiles(const AttnArgs& a, bool bwd) {
     const int64_t bh = (int64_t)a.B * a.nl, nblk = (a.S + BLK - 1) / BLK;
     if (nblk * bh >= cus) return NEVER;
     const int longest = (a.S + TILE - 1) / TILE;
-    for (int ch = 4; ch < longest; ++ch)
+    for (int ch = 8; ch < longest; ++ch)
         if (strip_slots(a.causal, false, a.S, make_chunk_len(ch)) * bh * 100 <= 105LL * cus) return ch;
     return NEVER;
 }
