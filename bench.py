@@ -320,6 +320,24 @@ def main():
     bwd_ms = timed(lambda: layer.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m,
                                           stream=stream), n_split)
 
+    # the same shard with the row-parallel epilogue on (bias + residual in the two row-parallel GEMMs, residual
+    # gradients in the two input-gradient GEMMs, db_o and db_dn): the headline rank runs with it off
+    flag_on = None
+    if not cfg.row_epilogue and not ckpt:
+        layer_on = pkg.TpLayer(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt,
+                               cfg.causal, True, cfg.head_dim, cfg.intermediate)
+        grads_on = layer_on.empty_grads()
+
+        def step_on():
+            layer_on.forward(p, x["x_a"], x["x_m"], y_a, y_m, stream=stream)
+            layer_on.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads_on, dx_a, dx_m, stream=stream)
+        step_on()
+        step_on()
+        on_ms = timed(step_on, n_split)
+        flag_on = {"ms_per_step": round(on_ms, 4), "value": round((f_fwd + f_bwd) / (on_ms * 1e-3) / 1e12, 2),
+                   "steps": n_split, "what": "same shard with the bias + residual epilogue of the row-parallel GEMMs on"}
+        del layer_on, grads_on
+
     # dominant kernel: the GEMM kernel.  Its 12 launches per step are timed inside real steps: the
     # library brackets each GEMM launch with HIP events on the launch stream (tp_layer_profile).
     roofline = None
@@ -410,6 +428,8 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu_baseline, "max_rel_err_vs_oracle": max_err,
         "input_gen_s": round(gen_s, 1),
     }
+    if flag_on is not None:
+        out["row_epilogue_on"] = flag_on
     print(json.dumps(out))
 
 
