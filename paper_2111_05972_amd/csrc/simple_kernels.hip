@@ -329,7 +329,7 @@ hipError_t attn_simple_bwd(const AttnArgs& a) {
 // Column sums (bias gradients): out[n] = sum_m X[m,n].  HBM-bound: X is read once with 16-byte loads.
 // Two fixed-order stages so results do not depend on scheduling: a block sums a slab of CS_ROWS rows
 // for 512 columns (64 column groups of 8 x 4 row lanes, combined through LDS in lane order) into
-// scratch[slab][n]; then one thread per column adds the slabs in order.
+// scratch[slab][n]; then the slabs of a column are added in a fixed order (four interleaved lanes).
 // ------------------------------------------------------------------------------------------------
 constexpr int CS_ROWS = 64;
 
@@ -343,7 +343,17 @@ __global__ __launch_bounds__(256) void colsum_stage1(int64_t M, int64_t N, const
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     const int cnt = n + 8 <= N ? 8 : (n < N ? (int)(N - n) : 0);     // columns this thread owns
     if (cnt == 8) {
-        for (int64_t m = m0 + rl; m < m1; m += 4) {
+        int64_t m = m0 + rl;
+        for (; m + 12 < m1; m += 16) {                               // four rows in flight, added in row order
+            float v[4][8];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) load8(X + (m + 4 * r) * N + n, v[r]);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += v[r][e];
+        }
+        for (; m < m1; m += 4) {
             float v[8];
             load8(X + m * N + n, v);
 #pragma unroll
@@ -361,15 +371,29 @@ __global__ __launch_bounds__(256) void colsum_stage1(int64_t M, int64_t N, const
         for (int e = 0; e < cnt; ++e) dst[e] = ((red[0][cg][e] + red[1][cg][e]) + red[2][cg][e]) + red[3][cg][e];
     }
 }
+// 64 columns x 4 slab lanes per workgroup: lane g adds slabs g, g+4, ... in order (four loads in flight), the four
+// lanes are combined through LDS in lane order.
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_stage2(int64_t slabs, int64_t N, int64_t stride,
                                                      const float* __restrict__ part,
                                                      T* __restrict__ out) {
-    int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (n >= N) return;
+    __shared__ float red[4][64];
+    const int cl = threadIdx.x & 63, gl = threadIdx.x >> 6;
+    const int64_t n = (int64_t)blockIdx.x * 64 + cl;
     float s = 0.0f;
-    for (int64_t i = 0; i < slabs; ++i) s += part[i * stride + n];
-    out[n] = from_f32<T>(s);
+    if (n < N) {
+        const float* src = part + n;
+        int64_t i = gl;
+        for (; i + 12 < slabs; i += 16) {
+            const float a = src[i * stride], b = src[(i + 4) * stride], c = src[(i + 8) * stride],
+                        d = src[(i + 12) * stride];
+            s += a; s += b; s += c; s += d;
+        }
+        for (; i < slabs; i += 4) s += src[i * stride];
+    }
+    red[gl][cl] = s;
+    __syncthreads();
+    if (gl == 0 && n < N) out[n] = from_f32<T>(((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl]);
 }
 
 size_t colsum_scratch_bytes(int64_t M, int64_t N) {
@@ -378,7 +402,7 @@ size_t colsum_scratch_bytes(int64_t M, int64_t N) {
 
 hipError_t sum_partials_strided(int dtype, int64_t slabs, int64_t N, const float* part, int64_t stride,
                                 void* out, hipStream_t s) {
-    dim3 g2((unsigned)((N + 255) / 256));
+    dim3 g2((unsigned)((N + 63) / 64));
     if (dtype == F32) hipLaunchKernelGGL(colsum_stage2<float>, g2, dim3(256), 0, s, slabs, N, stride, part, (float*)out);
     else hipLaunchKernelGGL(colsum_stage2<bf16_t>, g2, dim3(256), 0, s, slabs, N, stride, part, (bf16_t*)out);
     return hipGetLastError();
@@ -387,7 +411,7 @@ hipError_t sum_partials_strided(int dtype, int64_t slabs, int64_t N, const float
 hipError_t colsum(int dtype, int64_t M, int64_t N, const void* X, void* out, float* scratch,
                   hipStream_t s) {
     int64_t slabs = (M + CS_ROWS - 1) / CS_ROWS;
-    dim3 g1((unsigned)((N + 511) / 512), (unsigned)slabs), g2((unsigned)((N + 255) / 256));
+    dim3 g1((unsigned)((N + 511) / 512), (unsigned)slabs), g2((unsigned)((N + 63) / 64));
     if (dtype == F32) {
         hipLaunchKernelGGL(colsum_stage1<float>, g1, dim3(256), 0, s, M, N, (const float*)X, scratch);
         hipLaunchKernelGGL(colsum_stage2<float>, g2, dim3(256), 0, s, slabs, N, N, scratch, (float*)out);
