@@ -227,6 +227,8 @@ def main():
     ap.add_argument("--config", default="5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-row-epilogue-variant", action="store_true",
+                    help="skip the extra timing of the same shard with the row-parallel epilogue on")
     ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "ln", "memopt"],
                     help="layer: tp_layer_fwd + tp_layer_bwd (the headline metric); layer-checkpoint: tp_layer_fwd + "
                          "tp_layer_bwd_recompute; ln: replicated LayerNorm forward + backward on the config's [M, H]; "
@@ -323,7 +325,7 @@ def main():
     # the same shard with the row-parallel epilogue on (bias + residual in the two row-parallel GEMMs, residual
     # gradients in the two input-gradient GEMMs, db_o and db_dn): the headline rank runs with it off
     flag_on = None
-    if not cfg.row_epilogue and not ckpt:
+    if not cfg.row_epilogue and not ckpt and not args.no_row_epilogue_variant:
         layer_on = pkg.TpLayer(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt,
                                cfg.causal, True, cfg.head_dim, cfg.intermediate)
         grads_on = layer_on.empty_grads()
