@@ -14,8 +14,13 @@
 // dimension contiguous (V in forward, Q and dO in dK/dV, K in dQ) are read from LDS with the
 // transposing ds_read_b64_tr_b16.
 //
-// Backward is two kernels (dK/dV per key block, dQ per query block), each accumulating in registers
-// in a fixed order: no atomics, results are run-to-run identical.
+// Backward is a row-dot kernel (D = rowsum(dO * O)), a dK/dV kernel per key block and a dQ kernel per query
+// block, each accumulating in registers in a fixed order: no atomics, results are run-to-run identical.
+//
+// Streaming.  K/V (or Q/dO) tiles of 64 rows go from global memory straight into a two-stage LDS ring (buffer
+// loads with the LDS flag), the tile of step t+1 requested at the start of step t; fragments are read from LDS a
+// phase ahead of the MFMAs that use them.  A tile step is bound by vector arithmetic (exp2, scaling, conversions),
+// not by the matrix cores.
 //
 // Strips and chunks.  The tile steps of one (128-row block, head) form a strip; under the causal mask
 // strips are triangular (2 to S/64 steps) and the longest one is the critical path of the launch.  When
