@@ -108,6 +108,45 @@ def test_gemm_k_shares_own_choice(ta, tb, monkeypatch):
 ATTN_CASES = [(2, 128, 2, 64), (1, 300, 3, 128), (3, 77, 2, 32), (1, 1, 4, 64), (2, 513, 1, 64), (1, 1024, 2, 128)]
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_long_sequence_own_chunk_length(causal, monkeypatch):
+    """S = 4096 on two heads: far fewer strips than compute units, so with a workspace the library cuts them by
+    its own rule (several chunks per strip, also without a mask); forward and backward against the oracle."""
+    import torch
+    import paper_2111_05972_amd as pkg
+    monkeypatch.delenv("TPL_ATTN_CHUNK", raising=False)
+    B, S, nl, dh, dt, tol = 1, 4096, 2, 128, pkg.TPL_BF16, 2e-2
+    print(f"\n[attn] long S causal={causal} B={B} S={S} nl={nl} dh={dh}", flush=True)
+    nf, nb = (pkg.tp_layer_attn_workspace_bytes(dt, B, S, nl, dh, causal, bwd) for bwd in (False, True))
+    assert nf > 0 and nb > 0
+    qkv = _draw(900, (B * S, 3 * nl * dh), 1.0, "bf16")
+    d_o = _draw(901, (B * S, nl * dh), 1.0, "bf16")
+    t = qkv.reshape(B, S, 3, nl, dh).astype(np.float64)
+    Q, K, V = (t[:, :, i].transpose(0, 2, 1, 3) for i in range(3))
+    O, P, LSE = oracle.attention_fwd(Q, K, V, causal)
+    qkv_d = _t(qkv, dt)
+    o_d = torch.empty(B * S, nl * dh, dtype=qkv_d.dtype, device="cuda")
+    lse_d = torch.empty(B, nl, S, dtype=torch.float32, device="cuda")
+    ws_f = torch.full((nf // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    ws_b = torch.full((nb // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream()
+    pkg.tp_layer_attn_fwd(dt, B, S, nl, dh, causal, qkv_d, o_d, lse_d, ws=ws_f, stream=st)
+    torch.cuda.synchronize()
+    assert oracle.max_rel_err(o_d.float().cpu().numpy(), O.transpose(0, 2, 1, 3).reshape(B * S, nl * dh)) <= tol
+    assert np.abs(lse_d.cpu().numpy() - LSE).max() <= 2e-2
+    dO = d_o.reshape(B, S, nl, dh).transpose(0, 2, 1, 3).astype(np.float64)
+    dQ, dK, dV = oracle.attention_bwd(Q, K, V, P, dO)
+    ref = np.stack([a.transpose(0, 2, 1, 3) for a in (dQ, dK, dV)], axis=2).reshape(B * S, 3 * nl * dh)
+    dqkv_d = torch.empty_like(qkv_d)
+    scratch = torch.empty(B, nl, S, dtype=torch.float32, device="cuda")
+    pkg.tp_layer_attn_bwd(dt, B, S, nl, dh, causal, qkv_d, o_d, lse_d, _t(d_o, dt), dqkv_d, scratch, ws=ws_b, stream=st)
+    torch.cuda.synchronize()
+    got = dqkv_d.float().cpu().numpy()
+    for i, nm in enumerate(("dQ", "dK", "dV")):
+        sl = slice(i * nl * dh, (i + 1) * nl * dh)
+        assert oracle.max_rel_err(got[:, sl], ref[:, sl]) <= tol, nm
+
+
 # chunk: None = no workspace (strips never cut); "auto" = workspace, the library's own chunk length;
 # "1", "3" = workspace and chunks of that many 64-row tile steps (every strip longer than that is cut).
 @pytest.mark.parametrize("dtype,chunk", [("bf16", None), ("bf16", "auto"), ("bf16", "1"), ("bf16", "3"), ("f32", None)])
