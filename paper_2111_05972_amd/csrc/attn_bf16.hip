@@ -299,8 +299,10 @@ __global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(co
 #pragma unroll
             for (int ks = 0; ks < DH / 16; ++ks) fr[ks] = frag_k<DH>(ks_, kvh * 32, ks, lane);
             __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int ks = 0; ks < DH / 16; ++ks) s = MFMA(fr[ks], qf[ks], s);
+            __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int dt = 0; dt < DH / 32; ++dt) {
@@ -340,11 +342,13 @@ __global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(co
                     for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
             }
             bf16x8 pb0 = pack_regs(s, 0), pb1 = pack_regs(s, 8);
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int dt = 0; dt < DH / 32; ++dt) {
                 oacc[dt] = MFMA(fr[2 * dt], pb0, oacc[dt]);
                 oacc[dt] = MFMA(fr[2 * dt + 1], pb1, oacc[dt]);
             }
+            __builtin_amdgcn_s_setprio(0);
         }
         dma_wait();
         __syncthreads();
@@ -596,6 +600,7 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
 #pragma unroll
             for (int i = 0; i < W; ++i) fr[i] = fetch(i);
             __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int i = 0; i < NP; ++i) {
                 if (i < NF) s = MFMA(fr[i % W], kf[i], s);
@@ -603,6 +608,7 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
                 fr[i % W] = fetch(i + W);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            __builtin_amdgcn_s_setprio(0);
             const bool need_mask = qs0 + 31 >= S || k0 + 31 >= S || (CAUSAL && k0 + 31 > qs0);
             if (need_mask) {                          // wave-uniform: only tiles on the diagonal or at the end of S
 #pragma unroll
@@ -626,6 +632,7 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
                 }
             }
             bf16x8 g0 = pack_regs(s, 0), g1 = pack_regs(s, 8);
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int k = 0; k < NF; ++k) {
                 acc[k >> 1] = MFMA(fr[k % W], (k & 1) ? g1 : g0, acc[k >> 1]);
@@ -634,6 +641,7 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
         }
         if (more) r2s(nxt);
         dma_wait();
@@ -766,6 +774,7 @@ __global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __re
 #pragma unroll
             for (int i = 0; i < W; ++i) fr[i] = fetch(i);
             __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int i = 0; i < 2 * NF; ++i) {
                 if (i < NF) s = MFMA(fr[i % W], qf[i], s);
@@ -773,6 +782,7 @@ __global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __re
                 fr[i % W] = fetch(i + W);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            __builtin_amdgcn_s_setprio(0);
             const bool need_mask = q0 + 31 >= S || kv0 + 31 >= S || (CAUSAL && kv0 + 31 > q0);
             if (need_mask) {                          // wave-uniform: only tiles on the diagonal or at the end of S
 #pragma unroll
@@ -785,6 +795,7 @@ __global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __re
 #pragma unroll
             for (int v = 0; v < 16; ++v) dp[v] = fast_exp2(fmaf(s[v], c2, -l2)) * (dp[v] - dq_d);
             bf16x8 g0 = pack_regs(dp, 0), g1 = pack_regs(dp, 8);
+            __builtin_amdgcn_s_setprio(1);
 #pragma unroll
             for (int k = 0; k < NF; ++k) {
                 dq[k >> 1] = MFMA(fr[k % W], (k & 1) ? g1 : g0, dq[k >> 1]);
@@ -793,6 +804,7 @@ __global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __re
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
         }
         dma_wait();
         __syncthreads();
