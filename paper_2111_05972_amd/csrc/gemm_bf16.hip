@@ -265,57 +265,88 @@ __device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, 
 // Epilogue of one wavefront: accumulators -> its LDS staging area -> 16-byte row accesses.  The wavefront's
 // part of the tile goes through the staging area in slabs of 32 rows; store_slab(i, stage) writes slab i
 // (row r, column c of the wavefront's part at stage + r * EROW + 4 c).
+// One pass over a staged slab: 64 / LPR rows, 8 columns per lane (bias, residual, GeLU or its derivative, or the raw
+// float sums of one K share).
+template <typename TL>
+__device__ __forceinline__ void epilogue_pass(const GemmParams& p, const char* stage, int pass, int i, int wm, int lane,
+                                              int m0, int gn, const float (&bias8)[8], float* partial) {
+    constexpr int TM = TL::TM, TN = TL::TN;
+    constexpr int LPR = TN * 4;               // lanes per staged row (8 columns each)
+    constexpr int RPP = 64 / LPR;             // rows per pass (lanes beyond RPP*LPR idle when TN = 3)
+    const int er = lane / LPR, ec = (lane % LPR) * 8;
+    const int row = pass * RPP + er;
+    const int gm = m0 + (wm * TM + i) * 32 + row;
+    if (er < RPP && row < 32 && gm < p.M && gn < p.N) {
+        const float4* src = reinterpret_cast<const float4*>(stage + row * TL::EROW + ec * 4);
+        float4 x0 = src[0], x1 = src[1];
+        float v8[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+        const int64_t idx = (int64_t)gm * p.N + gn;
+        if (partial) {                     // one K share: the raw float sums; the epilogue is applied
+            float4* dst = reinterpret_cast<float4*>(partial + idx);   // when the shares are summed
+            dst[0] = x0; dst[1] = x1;
+            return;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v8[e] += bias8[e];
+        if (p.resid) {
+            float r8[8];
+            unpack8(*reinterpret_cast<const uint4*>(p.resid + idx), r8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v8[e] += r8[e];
+        }
+        if (p.epi == EPI_GELU) {
+            *reinterpret_cast<uint4*>(p.aux + idx) = pack8(v8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v8[e] = gelu_f(v8[e]);
+        } else if (p.epi == EPI_DGELU) {
+            float u8[8];
+            unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), u8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v8[e] *= gelu_grad_f(u8[e]);
+        }
+        *reinterpret_cast<uint4*>(p.C + idx) = pack8(v8);
+    }
+}
 template <typename TL, typename StoreSlab>
 __device__ __forceinline__ void epilogue_rows(const GemmParams& p, char* smem, int wave, int lane, int m0, int n0,
                                               float* partial, StoreSlab store_slab) {
     constexpr int TM = TL::TM, TN = TL::TN;
     const int wm = wave >> 1, wn = wave & 1;
-    constexpr int LPR = TN * 4;               // lanes per staged row (8 columns each)
-    constexpr int RPP = 64 / LPR;             // rows per pass (lanes beyond RPP*LPR idle when TN = 3)
-    constexpr int PASSES = (32 + RPP - 1) / RPP;
+    constexpr int LPR = TN * 4, RPP = 64 / LPR, PASSES = (32 + RPP - 1) / RPP;
     char* stage = smem + wave * TL::EWAVE;
-    const int er = lane / LPR, ec = (lane % LPR) * 8;
-    const int gn = n0 + wn * TN * 32 + ec;
+    const int gn = n0 + wn * TN * 32 + (lane % LPR) * 8;
     float bias8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (p.bias && !partial && gn < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + gn), bias8);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         store_slab(i, stage);
 #pragma unroll
-        for (int pass = 0; pass < PASSES; ++pass) {
-            const int row = pass * RPP + er;
-            const int gm = m0 + (wm * TM + i) * 32 + row;
-            if (er < RPP && row < 32 && gm < p.M && gn < p.N) {
-                const float4* src = reinterpret_cast<const float4*>(stage + row * TL::EROW + ec * 4);
-                float4 x0 = src[0], x1 = src[1];
-                float v8[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-                const int64_t idx = (int64_t)gm * p.N + gn;
-                if (partial) {                     // one K share: the raw float sums; the epilogue is applied
-                    float4* dst = reinterpret_cast<float4*>(partial + idx);   // when the shares are summed
-                    dst[0] = x0; dst[1] = x1;
-                    continue;
-                }
+        for (int pass = 0; pass < PASSES; ++pass) epilogue_pass<TL>(p, stage, pass, i, wm, lane, m0, gn, bias8, partial);
+    }
+}
+// The same for kernels whose fetching wavefronts 4..7 have nothing left to do: math wavefront w stages slab i into
+// one of two buffers, and after a workgroup barrier it and wavefront w + 4 (helper) take alternate passes over it.
+// Two buffers: the math wavefront stages slab i + 1 while its helper may still read slab i; buffer (i & 1) is
+// written again only after the barrier of slab i + 1, which the helper reaches after it has finished slab i.
+// Every wavefront of the workgroup executes exactly TM barriers here.
+template <typename TL, typename StoreSlab>
+__device__ __forceinline__ void epilogue_rows_shared(const GemmParams& p, char* smem, int wave, int lane, int m0, int n0,
+                                                     float* partial, bool helper, StoreSlab store_slab) {
+    constexpr int TM = TL::TM, TN = TL::TN;
+    const int w4 = wave & 3, wm = w4 >> 1, wn = w4 & 1;
+    constexpr int LPR = TN * 4, RPP = 64 / LPR, PASSES = (32 + RPP - 1) / RPP;
+    const int gn = n0 + wn * TN * 32 + (lane % LPR) * 8;
+    float bias8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (p.bias && !partial && gn < p.N) unpack8(*reinterpret_cast<const uint4*>(p.bias + gn), bias8);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v8[e] += bias8[e];
-                if (p.resid) {
-                    float r8[8];
-                    unpack8(*reinterpret_cast<const uint4*>(p.resid + idx), r8);
+    for (int i = 0; i < TM; ++i) {
+        char* stage = smem + (w4 * 2 + (i & 1)) * TL::EWAVE;
+        if (!helper) store_slab(i, stage);
+        __syncthreads();
+        // the helper takes the even passes (one more when their number is odd): the math wavefront also stages
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) v8[e] += r8[e];
-                }
-                if (p.epi == EPI_GELU) {
-                    *reinterpret_cast<uint4*>(p.aux + idx) = pack8(v8);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v8[e] = gelu_f(v8[e]);
-                } else if (p.epi == EPI_DGELU) {
-                    float u8[8];
-                    unpack8(*reinterpret_cast<const uint4*>(p.aux + idx), u8);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v8[e] *= gelu_grad_f(u8[e]);
-                }
-                *reinterpret_cast<uint4*>(p.C + idx) = pack8(v8);
-            }
-        }
+        for (int pass = 0; pass < PASSES; ++pass)
+            if (((pass & 1) == 0) == helper) epilogue_pass<TL>(p, stage, pass, i, wm, lane, m0, gn, bias8, partial);
     }
 }
 
@@ -348,6 +379,40 @@ __device__ __forceinline__ void epilogue16(const GemmParams& p, const f32x4 (&ac
                     *reinterpret_cast<float*>(stage + row * TL::EROW + (j * 16 + (lane & 15)) * 4) = acc[2 * i + ii][j][v];
                 }
     });
+}
+// Shared forms (see epilogue_rows_shared): the math wavefronts pass their accumulators, the helpers nothing.
+template <typename TL>
+__device__ __forceinline__ void epilogue_shared(const GemmParams& p, const f32x16 (&acc)[TL::TM][TL::TN], char* smem,
+                                                int wave, int lane, int m0, int n0, float* partial) {
+    epilogue_rows_shared<TL>(p, smem, wave, lane, m0, n0, partial, false, [&](int i, char* stage) {
+#pragma unroll
+        for (int j = 0; j < TL::TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int row = (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+                *reinterpret_cast<float*>(stage + row * TL::EROW + (j * 32 + (lane & 31)) * 4) = acc[i][j][v];
+            }
+    });
+}
+template <typename TL>
+__device__ __forceinline__ void epilogue16_shared(const GemmParams& p, const f32x4 (&acc)[2 * TL::TM][2 * TL::TN],
+                                                  char* smem, int wave, int lane, int m0, int n0, float* partial) {
+    epilogue_rows_shared<TL>(p, smem, wave, lane, m0, n0, partial, false, [&](int i, char* stage) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int j = 0; j < 2 * TL::TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    int row = ii * 16 + (lane >> 4) * 4 + v;
+                    *reinterpret_cast<float*>(stage + row * TL::EROW + (j * 16 + (lane & 15)) * 4) = acc[2 * i + ii][j][v];
+                }
+    });
+}
+template <typename TL>
+__device__ __forceinline__ void epilogue_helper(const GemmParams& p, char* smem, int wave, int lane, int m0, int n0,
+                                                float* partial) {
+    epilogue_rows_shared<TL>(p, smem, wave, lane, m0, n0, partial, true, [](int, char*) {});
 }
 
 template <typename TL, bool A_KMAJ, bool B_KMAJ>
@@ -669,7 +734,7 @@ struct SpecTile {
     static constexpr int EROW = TN * 32 * 4 + 16, EWAVE = 32 * EROW;     // epilogue staging, as in Tile
     template <bool A_KMAJ> static constexpr int a_bytes() { return A_KMAJ ? NA_WIDE * A_SLOT64 : NB * A_SLOT32; }
     template <bool A_KMAJ> static constexpr int lds_bytes() {
-        return a_bytes<A_KMAJ>() + NB * B_SLOT > 4 * EWAVE ? a_bytes<A_KMAJ>() + NB * B_SLOT : 4 * EWAVE;
+        return a_bytes<A_KMAJ>() + NB * B_SLOT > 8 * EWAVE ? a_bytes<A_KMAJ>() + NB * B_SLOT : 8 * EWAVE;   // 8: two staging buffers per math wavefront
     }
 };
 
@@ -788,6 +853,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
         }
         wait_vmcnt<0>();                                          // nothing lands in LDS during the epilogue
         __builtin_amdgcn_s_barrier();
+        epilogue_helper<ST>(p, smem, wave, lane, m0, n0, sh.partial);   // shares the rows of math wavefront wave - 4
         return;
     }
 
@@ -849,7 +915,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
-    epilogue<ST>(p, acc, smem, wave, lane, m0, n0, sh.partial);
+    epilogue_shared<ST>(p, acc, smem, wave, lane, m0, n0, sh.partial);
 }
 
 // Sum of the K shares in share order, then the epilogue; 8 columns per thread, every access 16 or 32 bytes.
@@ -976,6 +1042,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec16_kernel(GemmParams p) {
         }
         wait_vmcnt<0>();                                          // nothing lands in LDS during the epilogue
         __builtin_amdgcn_s_barrier();
+        epilogue_helper<ST>(p, smem, wave, lane, m0, n0, sh.partial);   // shares the rows of math wavefront wave - 4
         return;
     }
 
@@ -1073,7 +1140,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec16_kernel(GemmParams p) {
     mfma16_drain();
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
-    epilogue16<ST>(p, acc, smem, wave, lane, m0, n0, sh.partial);
+    epilogue16_shared<ST>(p, acc, smem, wave, lane, m0, n0, sh.partial);
 }
 
 // =================================================================================================
