@@ -14,8 +14,9 @@
 // dimension contiguous (V in forward, Q and dO in dK/dV, K in dQ) are read from LDS with the
 // transposing ds_read_b64_tr_b16.
 //
-// Backward is a row-dot kernel (D = rowsum(dO * O)), a dK/dV kernel per key block and a dQ kernel per query
-// block, each accumulating in registers in a fixed order: no atomics, results are run-to-run identical.
+// Backward is a row-dot kernel (D = rowsum(dO * O)) and one launch whose workgroups are dK/dV workgroups (per key
+// block) or dQ workgroups (per query block), each accumulating in registers in a fixed order: no atomics, results
+// are run-to-run identical.
 //
 // Streaming.  K/V (or Q/dO) tiles of 64 rows go from global memory straight into a two-stage LDS ring (buffer
 // loads with the LDS flag), the tile of step t+1 requested at the start of step t; fragments are read from LDS a
@@ -444,12 +445,14 @@ __global__ __launch_bounds__(256) void attn_fwd_combine_kernel(const float* __re
 template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_combine_kernel(const float* __restrict__ part_q,
                                                                const float* __restrict__ part_kv,
-                                                               bf16_t* __restrict__ dqkv, int S, int nl, int BH, ChunkLen ch,
+                                                               bf16_t* __restrict__ dqkv, int S, int nl, int BH,
+                                                               ChunkLen ch_q, ChunkLen ch_kv,
                                                                int blk0_q, int ncut_q, int blk0_kv, int ncut_kv) {
     constexpr int TPR = DH / 4, RPW = 256 / TPR, WPB = BLK / RPW;
     const int which = blockIdx.z;
     if ((int)blockIdx.x / WPB >= (which == 0 ? ncut_q : ncut_kv)) return;
-    const Chunk ck = find_chunk(CAUSAL, which != 0, S, ch, -1, (which == 0 ? blk0_q : blk0_kv) + (int)blockIdx.x / WPB);
+    const Chunk ck = find_chunk(CAUSAL, which != 0, S, which == 0 ? ch_q : ch_kv, -1,
+                                (which == 0 ? blk0_q : blk0_kv) + (int)blockIdx.x / WPB);
     if (ck.nch == 1) return;
     const int bh = blockIdx.y, b = bh / nl, h = bh % nl;
     const int psz = which == 0 ? BLK * DH : 2 * BLK * DH;
@@ -668,15 +671,13 @@ __device__ __forceinline__ void attn_dkv_body(char* smem, const bf16_t* __restri
     }
 }
 
+// dK/dV workgroup number wg (head fastest, then slot)
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(FTHREADS, 2) void attn_dkv_kernel(const bf16_t* __restrict__ qkv,
-                                                            const bf16_t* __restrict__ d_o,
-                                                            const float* __restrict__ lse,
-                                                            const float* __restrict__ dsum,
-                                                            bf16_t* __restrict__ dqkv, int S, int nl, int BH,
-                                                            float* __restrict__ part, ChunkLen ch) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int bh = blockIdx.x % BH, slot = blockIdx.x / BH;
+__device__ __forceinline__ void attn_dkv_wg(char* smem, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+                                            const float* __restrict__ lse, const float* __restrict__ dsum,
+                                            bf16_t* __restrict__ dqkv, int S, int nl, int BH,
+                                            float* __restrict__ part, ChunkLen ch, int wg) {
+    const int bh = wg % BH, slot = wg / BH;
     const Chunk ck = find_chunk(CAUSAL, true, S, ch, slot, 0);
     float* pslot = part + ((int64_t)slot * BH + bh) * (2 * BLK * DH);
     // the role is uniform per wavefront; both bodies run the same loop and the same barriers
@@ -695,19 +696,17 @@ template <int DH> constexpr int dq_lds_bytes() {
     return ring > merge ? ring : merge;
 }
 
+// dQ workgroup number wg (head fastest, then slot)
 template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __restrict__ qkv,
-                                                           const bf16_t* __restrict__ d_o,
-                                                           const float* __restrict__ lse,
-                                                           const float* __restrict__ dsum,
-                                                           bf16_t* __restrict__ dqkv, int S, int nl, int BH,
-                                                           float* __restrict__ part, ChunkLen ch) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+__device__ __forceinline__ void attn_dq_wg(char* smem, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+                                           const float* __restrict__ lse, const float* __restrict__ dsum,
+                                           bf16_t* __restrict__ dqkv, int S, int nl, int BH,
+                                           float* __restrict__ part, ChunkLen ch, int wg) {
     constexpr int TB = tile_bytes<DH>();
     constexpr int NCH = NCHUNKS<DH, FTHREADS>;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, half = lane >> 5;
     const int qs = wave & 3, kvh = wave >> 2;
-    const int bh = blockIdx.x % BH, slot = blockIdx.x / BH;
+    const int bh = wg % BH, slot = wg / BH;
     const Chunk ck = find_chunk(CAUSAL, false, S, ch, slot, 0);
     const int qb = ck.blk;
     const int b = bh / nl, h = bh % nl;
@@ -843,6 +842,26 @@ __global__ __launch_bounds__(FTHREADS, 2) void attn_dq_kernel(const bf16_t* __re
     }
 }
 
+// =================================================================================================
+// Backward in one launch: workgroups [0, wgs_kv) compute dK/dV chunks, the rest dQ chunks.  The two are independent,
+// both are bound by their longest strip rather than by the amount of work, and a compute unit holds one such
+// workgroup at a time: in one launch the units that finish the short chunks of one kind pick up chunks of the other
+// instead of idling until the launch ends.  dK/dV first: its steps are the longer ones.
+// =================================================================================================
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(FTHREADS, 2) void attn_bwd_kernel(const bf16_t* __restrict__ qkv,
+                                                               const bf16_t* __restrict__ d_o,
+                                                               const float* __restrict__ lse,
+                                                               const float* __restrict__ dsum,
+                                                               bf16_t* __restrict__ dqkv, int S, int nl, int BH,
+                                                               float* __restrict__ part_kv, float* __restrict__ part_q,
+                                                               ChunkLen ch_kv, ChunkLen ch_q, int wgs_kv) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int wg = blockIdx.x;                               // uniform: one kind per workgroup, its own barriers
+    if (wg < wgs_kv) attn_dkv_wg<DH, CAUSAL>(smem, qkv, d_o, lse, dsum, dqkv, S, nl, BH, part_kv, ch_kv, wg);
+    else attn_dq_wg<DH, CAUSAL>(smem, qkv, d_o, lse, dsum, dqkv, S, nl, BH, part_q, ch_q, wg - wgs_kv);
+}
+
 // ---- host side ----------------------------------------------------------------------------------
 bool attn_bf16_supported(const AttnArgs& a) {
     // tile loads address a (batch, head) slice with 32-bit byte offsets
@@ -857,32 +876,58 @@ static hipError_t set_lds(K kernel, int bytes) {
 }
 
 // Chunk length in tile steps.  No workspace: strips are never cut.  TPL_ATTN_CHUNK=<n> forces n (0: never cut).
-// Otherwise strips are cut only when there are fewer strips than compute units (with more, the units that finish
-// their short strips early pick up the queued ones, and cutting only adds the cost of the partials): the shortest
-// chunk length of at least 8 steps for which the chunks of all heads still run in one round (one workgroup per
-// compute unit, 5 % over allowed).  Every workgroup costs a few steps' worth of start-up and merge, so more and
-// shorter chunks than that measured slower.
-static int chunk_tiles(const AttnArgs& a, bool bwd) {
-    constexpr int NEVER = 1 << 30;
-    (void)bwd;
-    if (!a.ws) return NEVER;
+// Every workgroup costs a few steps' worth of start-up and merge and every cut strip its partials, so strips are
+// cut only where the longest one would otherwise set the duration, and never into chunks of fewer than 8 steps.
+constexpr int NEVER_CUT = 1 << 30;
+static bool forced_chunk(const AttnArgs& a, int* ch) {
+    if (!a.ws) { *ch = NEVER_CUT; return true; }
     if (const char* e = getenv("TPL_ATTN_CHUNK")) {
         const int v = atoi(e);
-        return v > 0 && v < (1 << 16) ? v : NEVER;
+        *ch = v > 0 && v < (1 << 16) ? v : NEVER_CUT;
+        return true;
     }
+    return false;
+}
+static int device_cus() {
     static int cus = 0;
     if (!cus) {
         int dev = 0;
         hipDeviceProp_t pr;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&pr, dev) != hipSuccess) return NEVER;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&pr, dev) != hipSuccess) return 0;
         cus = pr.multiProcessorCount;
     }
+    return cus;
+}
+// Forward (a launch of its own): only when there are fewer strips than compute units (with more, the units that
+// finish their short strips early pick up the queued ones): the shortest chunk length for which the chunks of all
+// heads still run in one round (one workgroup per compute unit, 5 % over allowed).
+static int chunk_tiles_fwd(const AttnArgs& a) {
+    int ch;
+    if (forced_chunk(a, &ch)) return ch;
+    const int cus = device_cus();
     const int64_t bh = (int64_t)a.B * a.nl, nblk = (a.S + BLK - 1) / BLK;
-    if (nblk * bh >= cus) return NEVER;
+    if (!cus || nblk * bh >= cus) return NEVER_CUT;
     const int longest = (a.S + TILE - 1) / TILE;
-    for (int ch = 8; ch < longest; ++ch)
+    for (ch = 8; ch < longest; ++ch)
         if (strip_slots(a.causal, false, a.S, make_chunk_len(ch)) * bh * 100 <= 105LL * cus) return ch;
-    return NEVER;
+    return NEVER_CUT;
+}
+// Backward: dK/dV and dQ workgroups share one launch, so the units that finish short strips of one kind pick up
+// strips of the other; with at least as many workgroups as compute units cutting measured no faster (the combine
+// kernel costs what the shorter critical path gains).  With fewer, the same rule as forward over both kinds.
+static int chunk_tiles_bwd(const AttnArgs& a, bool kv_side) {
+    int ch;
+    (void)kv_side;                              // one length for both kinds
+    if (forced_chunk(a, &ch)) return ch;
+    const int cus = device_cus();
+    const int64_t bh = (int64_t)a.B * a.nl, nblk = (a.S + BLK - 1) / BLK;
+    if (!cus || 2 * nblk * bh >= cus) return NEVER_CUT;
+    const int longest = (a.S + TILE - 1) / TILE;
+    for (ch = 8; ch < longest; ++ch) {
+        const ChunkLen c = make_chunk_len(ch);
+        if ((strip_slots(a.causal, false, a.S, c) + strip_slots(a.causal, true, a.S, c)) * bh * 100 <= 105LL * cus) return ch;
+    }
+    return NEVER_CUT;
 }
 static size_t part_bytes_fwd(const AttnArgs& a, ChunkLen ch) {
     return (size_t)strip_slots(a.causal, false, a.S, ch) * a.B * a.nl * BLK * (a.dh + 2) * sizeof(float);
@@ -910,9 +955,12 @@ static bool cuts(const AttnArgs& a, bool kv_side, ChunkLen ch) {
 size_t attn_bf16_workspace_bytes(const AttnArgs& a0, bool bwd) {
     AttnArgs a = a0;
     a.ws = reinterpret_cast<void*>(16);
-    const ChunkLen ch = make_chunk_len(chunk_tiles(a, bwd));
-    if (!bwd) return cuts(a, false, ch) ? part_bytes_fwd(a, ch) : 0;
-    return (cuts(a, false, ch) ? part_bytes_dq(a, ch) : 0) + (cuts(a, true, ch) ? part_bytes_dkv(a, ch) : 0);
+    if (!bwd) {
+        const ChunkLen ch = make_chunk_len(chunk_tiles_fwd(a));
+        return cuts(a, false, ch) ? part_bytes_fwd(a, ch) : 0;
+    }
+    const ChunkLen ch_q = make_chunk_len(chunk_tiles_bwd(a, false)), ch_kv = make_chunk_len(chunk_tiles_bwd(a, true));
+    return (cuts(a, false, ch_q) ? part_bytes_dq(a, ch_q) : 0) + (cuts(a, true, ch_kv) ? part_bytes_dkv(a, ch_kv) : 0);
 }
 
 template <int DH, bool CAUSAL>
@@ -924,7 +972,7 @@ static hipError_t fwd_t(const AttnArgs& a) {
         if (e != hipSuccess) return e;
         once = true;
     }
-    const ChunkLen ch = make_chunk_len(chunk_tiles(a, false));
+    const ChunkLen ch = make_chunk_len(chunk_tiles_fwd(a));
     if (a.ws && cuts(a, false, ch) && part_bytes_fwd(a, ch) > a.ws_bytes) return hipErrorInvalidValue;
     const int BH = a.B * a.nl;
     const int64_t wgs = (int64_t)strip_slots(CAUSAL, false, a.S, ch) * BH;
@@ -944,40 +992,37 @@ template <int DH, bool CAUSAL>
 static hipError_t bwd_t(const AttnArgs& a) {
     constexpr int LDS_KV = 2 * (2 * tile_bytes<DH>() + 2 * TILE * 4);
     constexpr int LDS_Q = dq_lds_bytes<DH>();
+    constexpr int LDS = LDS_KV > LDS_Q ? LDS_KV : LDS_Q;
     static bool once = false;
     if (!once) {
-        hipError_t e = set_lds(&attn_dkv_kernel<DH, CAUSAL>, LDS_KV);
-        if (e != hipSuccess) return e;
-        e = set_lds(&attn_dq_kernel<DH, CAUSAL>, LDS_Q);
+        hipError_t e = set_lds(&attn_bwd_kernel<DH, CAUSAL>, LDS);
         if (e != hipSuccess) return e;
         once = true;
     }
-    const ChunkLen ch = make_chunk_len(chunk_tiles(a, true));
-    const bool cut_q = cuts(a, false, ch), cut_kv = cuts(a, true, ch);
-    const size_t bytes_q = cut_q ? part_bytes_dq(a, ch) : 0, bytes_kv = cut_kv ? part_bytes_dkv(a, ch) : 0;
+    const ChunkLen ch_q = make_chunk_len(chunk_tiles_bwd(a, false)), ch_kv = make_chunk_len(chunk_tiles_bwd(a, true));
+    const bool cut_q = cuts(a, false, ch_q), cut_kv = cuts(a, true, ch_kv);
+    const size_t bytes_q = cut_q ? part_bytes_dq(a, ch_q) : 0, bytes_kv = cut_kv ? part_bytes_dkv(a, ch_kv) : 0;
     if (a.ws && bytes_q + bytes_kv > a.ws_bytes) return hipErrorInvalidValue;
     const int BH = a.B * a.nl;
-    const int64_t wgs_q = (int64_t)strip_slots(CAUSAL, false, a.S, ch) * BH;
-    const int64_t wgs_kv = (int64_t)strip_slots(CAUSAL, true, a.S, ch) * BH;
-    if (wgs_q > 0x7fffffffLL || wgs_kv > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int64_t wgs_q = (int64_t)strip_slots(CAUSAL, false, a.S, ch_q) * BH;
+    const int64_t wgs_kv = (int64_t)strip_slots(CAUSAL, true, a.S, ch_kv) * BH;
+    if (wgs_q + wgs_kv > 0x7fffffffLL) return hipErrorInvalidValue;
     float* part_q = static_cast<float*>(a.ws);
     float* part_kv = a.ws ? reinterpret_cast<float*>(static_cast<char*>(a.ws) + bytes_q) : nullptr;
     const int64_t rows = (int64_t)a.B * a.S;
     hipLaunchKernelGGL((attn_dsum_kernel<DH>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, a.stream,
                        (const bf16_t*)a.o, (const bf16_t*)a.d_o, a.dsum, a.B, a.S, a.nl);
-    hipLaunchKernelGGL((attn_dkv_kernel<DH, CAUSAL>), dim3((unsigned)wgs_kv), dim3(FTHREADS), LDS_KV, a.stream,
+    hipLaunchKernelGGL((attn_bwd_kernel<DH, CAUSAL>), dim3((unsigned)(wgs_kv + wgs_q)), dim3(FTHREADS), LDS, a.stream,
                        (const bf16_t*)a.qkv, (const bf16_t*)a.d_o, a.lse, a.dsum, (bf16_t*)a.dqkv, a.S, a.nl, BH,
-                       part_kv, ch);
-    hipLaunchKernelGGL((attn_dq_kernel<DH, CAUSAL>), dim3((unsigned)wgs_q), dim3(FTHREADS), LDS_Q, a.stream,
-                       (const bf16_t*)a.qkv, (const bf16_t*)a.d_o, a.lse, a.dsum, (bf16_t*)a.dqkv, a.S, a.nl, BH,
-                       part_q, ch);
+                       part_kv, part_q, ch_kv, ch_q, (int)wgs_kv);
     int blk0_q = 0, ncut_q = 0, blk0_kv = 0, ncut_kv = 0;
-    cut_range(a, false, ch, &blk0_q, &ncut_q);
-    cut_range(a, true, ch, &blk0_kv, &ncut_kv);
+    cut_range(a, false, ch_q, &blk0_q, &ncut_q);
+    cut_range(a, true, ch_kv, &blk0_kv, &ncut_kv);
     if (ncut_q || ncut_kv)
         hipLaunchKernelGGL((attn_bwd_combine_kernel<DH, CAUSAL>),
                            dim3((ncut_q > ncut_kv ? ncut_q : ncut_kv) * (BLK * DH / 1024), BH, 3), dim3(256), 0, a.stream,
-                           part_q, part_kv, (bf16_t*)a.dqkv, a.S, a.nl, BH, ch, blk0_q, ncut_q, blk0_kv, ncut_kv);
+                           part_q, part_kv, (bf16_t*)a.dqkv, a.S, a.nl, BH, ch_q, ch_kv, blk0_q, ncut_q, blk0_kv,
+                           ncut_kv);
     return hipGetLastError();
 }
 
