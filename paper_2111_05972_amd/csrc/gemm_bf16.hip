@@ -35,8 +35,8 @@
 //
 // Scheduling over the chip.  One workgroup per (output tile, K share).  Workgroup ids are dealt round-robin to
 // the 8 XCDs (each with its own L2), so ids are regrouped to give every XCD a contiguous run of tiles, and tiles
-// are ordered column-major inside bands of 8 tile rows: the tiles in flight on an XCD share operand panels in
-// that XCD's L2.
+// are ordered column-major inside bands of a few tile rows (the height that minimises what the tiles in flight on
+// an XCD fetch together, see choose_band): the tiles in flight on an XCD share operand panels in that XCD's L2.
 //
 // Epilogue.  Accumulators go through per-wavefront LDS staging so that every global access of the epilogue
 // (bias, residual, GeLU input, output) is a 16-byte access and a staged row is contiguous.
@@ -83,6 +83,7 @@ struct GemmParams {
     int lda, ldb;          // row strides (elements) of A and B as stored
     int epi;
     int tiles_m, tiles_n;
+    int band;              // tile rows per band of the tile order (see tile_coords)
     int nk;                // k-steps of one workgroup (one K share when K is split)
     int nk_total;          // k-steps of the whole K
     float* partial;        // K split over several workgroups: float partial sums [share][M][N], else null
@@ -250,15 +251,16 @@ __device__ __forceinline__ int share_of_block(int bid, int nblocks) {
     int xcd = bid % NXCD, idx = bid / NXCD;
     return xcd * per + (xcd < rem ? xcd : rem) + idx;
 }
-// Tile order: column-major inside bands of 8 tile rows, so tiles adjacent in the list (in flight
-// together on one XCD) share A and B panels in that XCD's L2.
-__device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, int& tm, int& tn) {
-    constexpr int BAND = 8;
-    int band_tiles = BAND * tiles_n;
+// Tile order: column-major inside bands of `band` tile rows.  Every XCD (own L2) works through one contiguous run
+// of this list (share_of_block), i.e. a block of band rows x some columns of the tile grid: it fetches the A panels
+// of its band and the B panels of its columns once.  The host picks the band height that minimises the sum over
+// XCDs of those fetches (choose_band).
+__device__ __forceinline__ void tile_coords(int tile, int tiles_m, int tiles_n, int band_rows, int& tm, int& tn) {
+    int band_tiles = band_rows * tiles_n;
     int band = tile / band_tiles, within = tile % band_tiles;
-    int rows = tiles_m - band * BAND;
-    rows = rows < BAND ? rows : BAND;
-    tm = band * BAND + within % rows;
+    int rows = tiles_m - band * band_rows;
+    rows = rows < band_rows ? rows : band_rows;
+    tm = band * band_rows + within % rows;
     tn = within / rows;
 }
 
@@ -430,7 +432,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
     constexpr int NM = TM * TN;                                   // matrix instructions per half stage
 
     int tm, tn;
-    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, p.band, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     f32x16 acc[TM][TN];
@@ -583,7 +585,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_x16w8_kernel(GemmParams p) {
     const int wq = wave_u & 3;
     const KShare sh = k_share(p, share_of_block(blockIdx.x, gridDim.x));
     int tm, tn;
-    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, p.band, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     // fetch state of this wavefront: descriptor, LDS position of its first block inside a stage, bytes per k,
@@ -757,7 +759,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const KShare sh = k_share(p, share_of_block(blockIdx.x, gridDim.x));   // sh.kt0 is even (host)
     int tm, tn;
-    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, p.band, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     if (wave >= 4) {
@@ -989,7 +991,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec16_kernel(GemmParams p) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const KShare sh = k_share(p, share_of_block(blockIdx.x, gridDim.x));   // sh.kt0 is even (host)
     int tm, tn;
-    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, p.band, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     if (wave >= 4) {
@@ -1168,7 +1170,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_x16s_kernel(GemmParams p) {
     const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
     const unsigned lds0 = (unsigned)(uintptr_t)(lds_void_ptr)smem;
     int tm, tn;
-    tile_coords(sh.tile, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(sh.tile, p.tiles_m, p.tiles_n, p.band, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
 
     f32x4 acc[FM][FN];
@@ -1334,6 +1336,27 @@ bool gemm_bf16_supported(const GemmArgs& a) {
     return tiles < (1 << 24) && a.K < (1 << 24);
 }
 
+// Band height of the tile order.  An XCD's L2 (4 MiB) holds no operand panel for long: what it saves is the reuse
+// among the tiles in flight on the XCD at one time, which walk K together: `inflight` consecutive tiles of the list =
+// h rows x inflight / h columns of the tile grid, needing h A slices and inflight / h B slices per k-step.  The band
+// height minimises h * bm + (inflight / h) * bn.  TPL_GEMM_BAND=<h> forces a height.
+static int choose_band(int R, int bm, int bn, int lds_bytes) {
+    if (const char* e = getenv("TPL_GEMM_BAND")) {
+        const int v = atoi(e);
+        if (v > 0) return v;
+    }
+    const int inflight = 32 * (lds_bytes <= 80 * 1024 ? 2 : 1);      // 32 compute units per XCD
+    int best = 1;
+    double best_cost = 1e300;
+    for (int h = 1; h <= inflight; h *= 2) {
+        const int hh = h < R ? h : R;
+        const double cost = (double)hh * bm + (double)inflight / hh * bn;
+        if (cost < best_cost) { best_cost = cost; best = hh; }
+        if (h >= R) break;
+    }
+    return best;
+}
+
 template <typename TL, bool AK, bool BK_>
 static hipError_t launch(GemmParams p, const GemmArgs& a, int shares) {
     static bool attr_set = false;   // raising the dynamic LDS limit is a per-function, one-off call
@@ -1345,6 +1368,7 @@ static hipError_t launch(GemmParams p, const GemmArgs& a, int shares) {
     }
     p.tiles_m = (int)((a.M + TL::BM - 1) / TL::BM);
     p.tiles_n = (int)((a.N + TL::BN - 1) / TL::BN);
+    p.band = choose_band(p.tiles_m, TL::BM, TL::BN, TL::LDS_BYTES);
     hipLaunchKernelGGL((gemm_bf16_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(256),
                        TL::LDS_BYTES, a.stream, p);
     return hipGetLastError();
@@ -1370,6 +1394,7 @@ static hipError_t launch_x16s(GemmParams p, const GemmArgs& a, int shares) {
     }
     p.tiles_m = (int)((a.M + TL::BM - 1) / TL::BM);
     p.tiles_n = (int)((a.N + TL::BN - 1) / TL::BN);
+    p.band = choose_band(p.tiles_m, TL::BM, TL::BN, TL::LDS_BYTES);
     hipLaunchKernelGGL((gemm_bf16_x16s_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(256),
                        TL::LDS_BYTES, a.stream, p);
     return hipGetLastError();
@@ -1394,6 +1419,7 @@ static hipError_t launch_w8(GemmParams p, const GemmArgs& a, int shares) {
     }
     p.tiles_m = (int)((a.M + TL::BM - 1) / TL::BM);
     p.tiles_n = (int)((a.N + TL::BN - 1) / TL::BN);
+    p.band = choose_band(p.tiles_m, TL::BM, TL::BN, TL::LDS_BYTES);
     hipLaunchKernelGGL((gemm_bf16_x16w8_kernel<TL, AK, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(512),
                        TL::LDS_BYTES, a.stream, p);
     return hipGetLastError();
@@ -1419,6 +1445,7 @@ static hipError_t launch_spec(GemmParams p, const GemmArgs& a, int shares) {
     }
     p.tiles_m = (int)((a.M + ST::BM - 1) / ST::BM);
     p.tiles_n = (int)((a.N + ST::BN - 1) / ST::BN);
+    p.band = choose_band(p.tiles_m, ST::BM, ST::BN, LDS);
     hipLaunchKernelGGL((gemm_bf16_spec_kernel<ST, AK, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(512), LDS, a.stream, p);
     return hipGetLastError();
 }
@@ -1434,6 +1461,7 @@ static hipError_t launch_spec16(GemmParams p, const GemmArgs& a, int shares) {
     }
     p.tiles_m = (int)((a.M + ST::BM - 1) / ST::BM);
     p.tiles_n = (int)((a.N + ST::BN - 1) / ST::BN);
+    p.band = choose_band(p.tiles_m, ST::BM, ST::BN, LDS);
     hipLaunchKernelGGL((gemm_bf16_spec16_kernel<ST, BK_>), dim3(p.tiles_m * p.tiles_n * shares), dim3(512), LDS, a.stream, p);
     return hipGetLastError();
 }
@@ -1537,6 +1565,7 @@ hipError_t gemm_bf16(const GemmArgs& a) {
     p.ldb = a.trans_b ? (int)a.K : (int)a.N;
     p.epi = a.epi;
     p.tiles_m = p.tiles_n = 0;
+    p.band = 8;
     const Plan pl = make_plan(a.M, a.N, a.K, !a.trans_a, a.trans_b != 0);
     p.nk_total = (int)((a.K + DK - 1) / DK);
     p.nk = pl.nk_share;
