@@ -38,6 +38,7 @@ struct AttnArgs {
     float* dsum;       // bwd only: [B, nl, S] scratch, rowsum(dO * O)
     void* ws;          // optional (bf16 kernels): float partials that let long strips be cut into chunks
     size_t ws_bytes;
+    int own_chunking;  // 1: the kernels may cut strips by their own rule; 0: only when TPL_ATTN_CHUNK forces a length
     hipStream_t stream;
 };
 

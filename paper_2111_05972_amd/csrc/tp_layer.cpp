@@ -67,7 +67,8 @@ size_t gemm_ws(int dtype, int64_t M, int64_t N, int64_t K) {
 // Backward scratch: dU, dO, dQKV, D, and per chain (attention, MLP) column-sum partials and GEMM scratch.
 struct BwdWs { size_t du, d_o, dqkv, dsum, colsum, colsum2, gemm, gemm2, gemm_each, attn, attn_bytes, total; };
 
-// Float partials that let the attention kernels cut long strips into chunks (0 when they would not).
+// Float partials of attention strips cut into chunks: inside a layer pass only when TPL_ATTN_CHUNK forces a chunk
+// length (own_chunking stays 0: see attn_bf16.hip), so normally 0.
 size_t attn_ws(const Dims& x, bool bwd) {
     AttnArgs a{};
     a.dtype = x.dtype; a.B = (int)x.B; a.S = (int)x.S; a.nl = (int)x.nl; a.dh = (int)x.dh; a.causal = x.causal;
@@ -573,7 +574,7 @@ static int attn_check(int dtype, int B, int S, int nl, int dh) {
 size_t tp_layer_attn_workspace_bytes(int dtype, int B, int S, int nl, int dh, int causal, int bwd) {
     if (attn_check(dtype, B, S, nl, dh)) return 0;
     AttnArgs a{};
-    a.dtype = dtype; a.B = B; a.S = S; a.nl = nl; a.dh = dh; a.causal = causal != 0;
+    a.dtype = dtype; a.B = B; a.S = S; a.nl = nl; a.dh = dh; a.causal = causal != 0; a.own_chunking = 1;
     if (dtype != BF16 || !attn_bf16_supported(a)) return 0;
     return up(attn_bf16_workspace_bytes(a, bwd != 0));
 }
@@ -587,7 +588,8 @@ int tp_layer_attn_fwd(int dtype, int B, int S, int nl, int dh, int causal, const
     if (ws && ws_bytes < tp_layer_attn_workspace_bytes(dtype, B, S, nl, dh, causal, 0)) return TPL_EWORKSPACE;
     AttnArgs a{};
     a.dtype = dtype; a.B = B; a.S = S; a.nl = nl; a.dh = dh; a.causal = causal != 0;
-    a.qkv = qkv; a.o = o; a.lse = lse; a.ws = ws; a.ws_bytes = ws_bytes; a.stream = (hipStream_t)hip_stream;
+    a.qkv = qkv; a.o = o; a.lse = lse; a.ws = ws; a.ws_bytes = ws_bytes; a.own_chunking = 1;
+    a.stream = (hipStream_t)hip_stream;
     return run_attn(a, false);
 }
 
@@ -603,7 +605,8 @@ int tp_layer_attn_bwd(int dtype, int B, int S, int nl, int dh, int causal, const
     AttnArgs a{};
     a.dtype = dtype; a.B = B; a.S = S; a.nl = nl; a.dh = dh; a.causal = causal != 0;
     a.qkv = qkv; a.o = const_cast<void*>(o); a.lse = const_cast<float*>(lse); a.d_o = d_o;
-    a.dqkv = dqkv; a.dsum = d_scratch; a.ws = ws; a.ws_bytes = ws_bytes; a.stream = (hipStream_t)hip_stream;
+    a.dqkv = dqkv; a.dsum = d_scratch; a.ws = ws; a.ws_bytes = ws_bytes; a.own_chunking = 1;
+    a.stream = (hipStream_t)hip_stream;
     return run_attn(a, true);
 }
 
