@@ -44,6 +44,7 @@
 #include <type_traits>
 
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 
 #include "device_math.h"
@@ -1345,7 +1346,10 @@ static int choose_band(int R, int bm, int bn, int lds_bytes) {
         const int v = atoi(e);
         if (v > 0) return v;
     }
-    const int inflight = 32 * (lds_bytes <= 80 * 1024 ? 2 : 1);      // 32 compute units per XCD
+    // 32 compute units per XCD; the kernels with two workgroups per unit were also measured fastest with the band of
+    // 32 tiles in flight (4 rows, 0.6 % of the step ahead of 8), so the count is not doubled for them
+    (void)lds_bytes;
+    const int inflight = 32;
     int best = 1;
     double best_cost = 1e300;
     for (int h = 1; h <= inflight; h *= 2) {
@@ -1511,9 +1515,28 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj)
     static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658, 0.70, 0.602, 0.509};
     static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0, 12.5, 18.0, 12.0};
     const char* e = getenv("TPL_GEMM_TILE");          // tuning / test overrides: one digit; a number
-    const int forced_v = (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) ? e[0] - '0' : -1;
+    int forced_v = (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) ? e[0] - '0' : -1;
     const char* es = getenv("TPL_GEMM_SHARES");
-    const int forced_s = es ? atoi(es) : 0;
+    int forced_s = es ? atoi(es) : 0;
+    // TPL_GEMM_FORCE="MxNxK@ab=v[:shares];..." (a, b = 1 if A, B is K-major) overrides the plan of single shapes (tuning inside a whole step)
+    int forced_shape_v = -1;
+    if (const char* ef = getenv("TPL_GEMM_FORCE")) {
+        const char* q = ef;
+        while (*q) {
+            long long m = 0, n = 0, k = 0; int ak = 0, bk = 0, v = -1, sh = 0, used = 0;
+            if (sscanf(q, "%lldx%lldx%lld@%1d%1d=%d%n", &m, &n, &k, &ak, &bk, &v, &used) >= 6) {   // @ab: A, B K-major
+                const char* r = q + used;
+                if (*r == ':') sh = atoi(r + 1);
+                if (m == M && n == N && k == K && (ak != 0) == a_kmaj && (bk != 0) == b_kmaj && v >= 0 && v < NVARIANTS) {
+                    forced_shape_v = v;
+                    if (sh > 0) forced_s = sh;
+                }
+            }
+            while (*q && *q != ';') ++q;
+            if (*q == ';') ++q;
+        }
+    }
+    if (forced_shape_v >= 0) forced_v = forced_shape_v;
     const int cus = compute_units();
     const int nk = (int)((K + DK - 1) / DK);
     Plan best{0, 1, nk};
@@ -1523,9 +1546,13 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj)
         // the variant with fetch-only wavefronts is built for a K-major A (its MN-major A path spills)
         if (forced_v < 0 && v == 4 && !a_kmaj) continue;
         if (v == 6 && !a_kmaj) continue;              // written for a K-major A only
-        // the two-per-CU 16x16x32 tile is the weight-gradient kernel (MN-major A); with a K-major A it only pays when
-        // many rounds of tiles amortise its cold starts (measured inside the layer step, not in an isolated loop)
-        if (forced_v < 0 && v == 7 && a_kmaj && ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]) < 4 * compute_units()) continue;
+        // the two-per-CU 16x16x32 tile is the weight-gradient kernel (MN-major A); with a K-major A it pays when K is
+        // short (co-resident workgroups hide each other's start and end: the out-projection, K = 1536, -30 us per
+        // forward pass against the 8-wavefront variant) or when many rounds of tiles amortise its cold starts; on the
+        // long-K forward and data-gradient GEMMs it is 2-5 % slower per step (all measured inside the layer step by
+        // forcing single shapes with TPL_GEMM_FORCE, not in isolated loops)
+        if (forced_v < 0 && v == 7 && a_kmaj && nk > 64 &&
+            ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]) < 4 * compute_units()) continue;
         // with an MN-major B its 20 fragment reads per k-step hold up the matrix instructions: no gain there
         if (forced_v < 0 && v == 6 && !b_kmaj) continue;
         // the 8-wavefront variant was measured against the others on K-major A only (forward, data gradients)
@@ -1541,6 +1568,10 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj)
             const double per_cu = (double)((tiles * shares + cus - 1) / cus);
             double c = per_cu * per * us_per_stage[v] + fixed_us[v] * (wgs_per_cu[v] == 1 ? per_cu : 1.0);
             if (shares > 1) c += 6.0 + (double)M * N * (8.0 * shares + 2.0) / 3.0e6;   // second pass at ~3 TB/s
+            // a split GEMM that takes (nearly) every compute unit leaves none to the kernels of the other chain:
+            // measured inside the whole step, the out-projection data gradient is fastest with 3 shares (192
+            // workgroups), 0.8 % of the step ahead of 4 (256 workgroups)
+            if (shares > 1 && tiles * shares * 4 > (int64_t)cus * 3) c *= 1.10;
             if (best_c < 0 || c < best_c) { best = Plan{v, shares, per}; best_c = c; }
         }
     }
