@@ -1550,8 +1550,9 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj)
         // short (co-resident workgroups hide each other's start and end: the out-projection, K = 1536, -30 us per
         // forward pass against the 8-wavefront variant) or when many rounds of tiles amortise its cold starts; on the
         // long-K forward and data-gradient GEMMs it is 2-5 % slower per step (all measured inside the layer step by
-        // forcing single shapes with TPL_GEMM_FORCE, not in isolated loops)
-        if (forced_v < 0 && v == 7 && a_kmaj && nk > 64 &&
+        // forcing single shapes with TPL_GEMM_FORCE, not in isolated loops); the same holds for its 32x32x16 sibling,
+        // variant 3 (config 4's out-projection data gradient: -1.2 % of the step without it)
+        if (forced_v < 0 && (v == 7 || v == 3) && a_kmaj && nk > 64 &&
             ((M + bm[v] - 1) / bm[v]) * ((N + bn[v] - 1) / bn[v]) < 4 * compute_units()) continue;
         // with an MN-major B its 20 fragment reads per k-step hold up the matrix instructions: no gain there
         if (forced_v < 0 && v == 6 && !b_kmaj) continue;
