@@ -5,8 +5,9 @@
 //                             192x192 / 128x128 with two workgroups per compute unit
 //   gemm_bf16_spec_kernel     256x192, 4 math + 4 fetch wavefronts, MFMA 32x32x16      (forward GEMMs: NN)
 //   gemm_bf16_spec16_kernel   the same roles on MFMA 16x16x32, K-major A               (data gradients: NT)
-//   gemm_bf16_x16s_kernel     192x192, two workgroups per compute unit, MFMA 16x16x32  (weight gradients: TN)
-//   gemm_bf16_x16w8_kernel    256x192, 8 wavefronts that fetch and compute, 16x16x32   (short K)
+//   gemm_bf16_x16s_kernel     192x192, two workgroups per compute unit, MFMA 16x16x32  (weight gradients: TN; short-K
+//                             forward GEMMs such as the out-projection)
+//   gemm_bf16_x16w8_kernel    256x192, 8 wavefronts that fetch and compute, 16x16x32   (short K, one GEMM at a time)
 //   gemm_sum_shares_kernel    adds the partial sums of a GEMM whose K was cut into shares, applies the epilogue
 //
 // Pipeline.  K is walked in stages of 32 through LDS rings filled by buffer_load ... lds: global memory goes
