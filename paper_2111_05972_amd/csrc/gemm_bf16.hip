@@ -86,6 +86,7 @@ struct GemmParams {
     int epi;
     int tiles_m, tiles_n;
     int band;              // tile rows per band of the tile order (see tile_coords)
+    int nt_store;          // C stored with the non-temporal hint
     int nk;                // k-steps of one workgroup (one K share when K is split)
     int nk_total;          // k-steps of the whole K
     float* partial;        // K split over several workgroups: float partial sums [share][M][N], else null
@@ -308,7 +309,14 @@ __device__ __forceinline__ void epilogue_pass(const GemmParams& p, const char* s
 #pragma unroll
             for (int e = 0; e < 8; ++e) v8[e] *= gelu_grad_f(u8[e]);
         }
-        *reinterpret_cast<uint4*>(p.C + idx) = pack8(v8);
+        const uint4 out = pack8(v8);
+        if (p.nt_store) {
+            typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+            u32x4 o4 = {out.x, out.y, out.z, out.w};
+            __builtin_nontemporal_store(o4, reinterpret_cast<u32x4*>(p.C + idx));
+        } else {
+            *reinterpret_cast<uint4*>(p.C + idx) = out;
+        }
     }
 }
 template <typename TL, typename StoreSlab>
@@ -1594,6 +1602,7 @@ hipError_t gemm_bf16(const GemmArgs& a) {
     p.A = (const bf16_t*)a.A; p.B = (const bf16_t*)a.B; p.C = (bf16_t*)a.C;
     p.bias = (const bf16_t*)a.bias; p.resid = (const bf16_t*)a.resid; p.aux = (bf16_t*)a.aux;
     p.M = (int)a.M; p.N = (int)a.N; p.K = (int)a.K;
+    p.nt_store = a.c_streaming ? 1 : 0;
     p.lda = a.trans_a ? (int)a.M : (int)a.K;
     p.ldb = a.trans_b ? (int)a.K : (int)a.N;
     p.epi = a.epi;

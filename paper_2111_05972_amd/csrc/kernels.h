@@ -24,6 +24,7 @@ struct GemmArgs {
     void* ws;
     size_t ws_bytes;
     hipStream_t stream;
+    bool c_streaming;   // C is not read again soon (weight gradients): store it with the non-temporal hint
 };
 
 struct AttnArgs {

@@ -327,8 +327,10 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     b5.aux = const_cast<void*>(u); b5.epi = EPI_DGELU;
     if ((rc = run_gemm(b5))) return rc;
     GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, sc2);
+    w5.c_streaming = true;                   // the weight gradient is not read again in this pass
     if ((rc = run_gemm(w5))) return rc;
     GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, sc2);
+    w4.c_streaming = true;                   // the weight gradient is not read again in this pass
     if ((rc = run_gemm(w4))) return rc;
     if (colsum(x.dtype, x.M, x.Il, du, gr->db_up, cs2, s2) != hipSuccess) return TPL_EHIP;
     GemmArgs d4 = mk(x, 0, 1, x.M, x.H, x.Il, du, p->w_up, dx_mlp, sc2);
@@ -340,6 +342,7 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     GemmArgs d3 = mk(x, 0, 1, x.M, x.Hl, x.H, dy_attn, p->w_o, d_o, sc);
     if ((rc = run_gemm(d3))) return rc;
     GemmArgs w3 = mk(x, 1, 0, x.Hl, x.H, x.M, o, dy_attn, gr->dw_o, sc);
+    w3.c_streaming = true;                   // the weight gradient is not read again in this pass
     if ((rc = run_gemm(w3))) return rc;
     if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_attn, gr->db_o, cs, s) != hipSuccess) return TPL_EHIP;
     AttnArgs at{};
@@ -350,6 +353,7 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     at.ws = W.attn_bytes ? w + W.attn : nullptr;
     if ((rc = run_attn(at, true))) return rc;
     GemmArgs w1 = mk(x, 1, 0, x.H, 3 * x.Hl, x.M, x_attn, dqkv, gr->dw_qkv, sc);
+    w1.c_streaming = true;                   // the weight gradient is not read again in this pass
     if ((rc = run_gemm(w1))) return rc;
     if (colsum(x.dtype, x.M, 3 * x.Hl, dqkv, gr->db_qkv, cs, s) != hipSuccess) return TPL_EHIP;
     GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, sc);
