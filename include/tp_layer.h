@@ -30,15 +30,20 @@
  * Ownership.  The caller owns every buffer, including `saved` and `ws`; the library allocates no
  * device memory, never synchronises with the host, and orders all work on `hip_stream` (a
  * hipStream_t passed as void*; NULL = the default stream): work enqueued on `hip_stream` before a
- * call happens before it, work enqueued after the call happens after it.  Inside tp_layer_fwd and
- * tp_layer_bwd the attention block and the MLP block, which share no tensor, run as two chains,
- * the second on a stream the library creates once per device (default priority) and forks from /
- * joins to `hip_stream` with events; TPL_SINGLE_STREAM=1 in the environment keeps everything on
- * `hip_stream`.  That second stream and its events are shared by all calls on a device: host
- * threads that call tp_layer_fwd / tp_layer_bwd on the same device at the same time must
- * serialise their calls (or set TPL_SINGLE_STREAM=1).  Pointers must be 16-byte aligned.  Outputs must not alias inputs.  Gradients are
- * overwritten, not accumulated.  `ws` contents need not be preserved between calls; calls that
- * share a `ws` must be stream-ordered.
+ * call happens before it, work enqueued after the call happens after it.  By default every kernel
+ * of a call is enqueued on `hip_stream` itself.  With TPL_SIDE_STREAM in the descriptor's flags,
+ * tp_layer_fwd / tp_layer_bwd / tp_layer_bwd_recompute enqueue the attention block and the MLP
+ * block, which share no tensor, as two chains, the second on a stream the library creates once per
+ * device (default priority) and forks from / joins to `hip_stream` with events (also when the call
+ * fails half-way).  That second stream and its events are shared by all calls on a device: host
+ * threads that make such calls on the same device at the same time must serialise them.
+ * Pointers must be 16-byte aligned.  Outputs must not alias inputs.  Gradients are overwritten,
+ * not accumulated.  `ws` contents need not be preserved between calls; calls that share a `ws`
+ * must be stream-ordered.
+ *
+ * Environment.  Nothing on a launch path reads the environment.  The tuning overrides
+ * TPL_GEMM_TILE, TPL_GEMM_SHARES, TPL_GEMM_BAND, TPL_GEMM_FORCE and TPL_ATTN_CHUNK are read once,
+ * when the library is first used, as initial values of the options of tp_layer_set_option.
  *
  * Errors.  Every entry point returns a tpl_status and never aborts; arguments are validated
  * before anything is enqueued.
@@ -66,7 +71,8 @@ typedef enum { TPL_F32 = 0, TPL_BF16 = 1 } tpl_dtype;
 
 enum {
     TPL_CAUSAL = 1u,       /* query i attends keys j <= i (else no mask); Sec. I.4 `causal_mask_size` */
-    TPL_ROW_EPILOGUE = 2u  /* this rank adds b_o, b_dn and the residual (tp_rank 0 by the Fig. 7 rule) */
+    TPL_ROW_EPILOGUE = 2u, /* this rank adds b_o, b_dn and the residual (tp_rank 0 by the Fig. 7 rule) */
+    TPL_SIDE_STREAM = 4u   /* scheduling only: run the two blocks of a pass as two chains (see Ownership) */
 };
 
 /* The layer and this rank's place in it (App. F.1; constructor arguments of
@@ -81,7 +87,7 @@ typedef struct {
     int32_t seq;           /* S                                                    */
     int32_t micro_batch;   /* B                                                    */
     int32_t dtype;         /* tpl_dtype                                            */
-    uint32_t flags;        /* TPL_CAUSAL | TPL_ROW_EPILOGUE                        */
+    uint32_t flags;        /* TPL_CAUSAL | TPL_ROW_EPILOGUE | TPL_SIDE_STREAM      */
 } tp_layer_desc;
 
 /* This rank's parameter shard (device pointers, read-only).  b_o and b_dn may be NULL unless
@@ -249,8 +255,8 @@ int tp_layer_gemm(int dtype, int trans_a, int trans_b, int64_t M, int64_t N, int
  * order by a second kernel (float partials in ws): the causal mask makes those strips triangular
  * and the longest one would otherwise set the duration of the launch.  Results are deterministic
  * either way; they differ between the two ways by float rounding only.  A non-NULL ws that is too
- * small gives TPL_EWORKSPACE.  TPL_ATTN_CHUNK=<n> in the environment forces chunks of n 64-row tile
- * steps (0: never cut); it must not change between the size query and the call. */
+ * small gives TPL_EWORKSPACE.  The option attn_chunk = n (tp_layer_set_option) forces chunks of n
+ * 64-row tile steps (0: never cut); it must not change between the size query and the call. */
 size_t tp_layer_attn_workspace_bytes(int dtype, int B, int S, int nl, int dh, int causal, int bwd);
 int tp_layer_attn_fwd(int dtype, int B, int S, int nl, int dh, int causal,
                       const void* qkv, void* o, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
@@ -266,6 +272,17 @@ int tp_layer_attn_bwd(int dtype, int B, int S, int nl, int dh, int causal,
  * durations in milliseconds to ms_out[0..*count) and restarts the record.  ms_out is HOST memory. */
 int tp_layer_profile(int enable);
 int tp_layer_profile_read(float* ms_out, int capacity, int* count);
+
+/* Tuning overrides, for tests (which run every kernel variant through them) and for tuning; process-wide, not
+ * thread-safe, and they must not change between a workspace-size query and the call it sizes.  name:
+ *   "gemm_tile"   force one GEMM tile variant (0..7) for every bf16 GEMM
+ *   "gemm_shares" force the number of K shares of every bf16 GEMM
+ *   "gemm_band"   force the band height of the GEMM tile order
+ *   "gemm_force"  "MxNxK@ab=v[:shares];..." plans for single shapes (a, b = 1 where A, B has K contiguous)
+ *   "attn_chunk"  chunk length of attention strips in 64-row tile steps (0: never cut)
+ * value: decimal text; NULL or "" returns the option to "let the library choose".  TPL_EINVAL for an unknown
+ * name or a value that does not parse. */
+int tp_layer_set_option(const char* name, const char* value);
 
 /* Static description of a status code. */
 const char* tp_layer_strerror(int status);

@@ -21,7 +21,7 @@ Each function is the definition written out with numpy in float64; matmul is the
 only library primitive used as a step.
 
 The paper's figures of this mode are missing from its text, so the order of the
-pieces inside a block is a reading (listed in the design notes): pre-normalised
+pieces inside a block is a reading: pre-normalised
 blocks, y = x + Block(LN(x)), with the bias of an input-split linear (and the
 residual) added once, after the reduce-scatter, by the rank that keeps that slice.
 
@@ -30,7 +30,13 @@ textbook layer normalisation of the full rows (np.mean / np.var) and PyTorch's
 F.layer_norm; the sliced backward equals central finite differences of the full-row
 normalisation; T simulated ranks joined by the collectives equal the unsharded
 reference layer, forward and backward (finite differences on the unsharded one);
-bias+GeLU closed forms.  No function here is unpinned.
+bias+GeLU closed forms; this module's own attention (`_attention`, `_attention_bwd`)
+against the scalar definition by plain loops, a hand-computed two-key case that fixes
+the 1/sqrt(dh) scale and the mask diagonal, PyTorch's CPU scaled_dot_product_attention
+with autograd, and the speed-optimised oracle's attention; `reference_layer_fwd` against
+the pre-normalised layer written with PyTorch's CPU operators; planted mistakes (no
+scale, mask without the diagonal, a wrong dK, a post-normalised reference) each make a
+pin fail.  No function here is unpinned.
 """
 import numpy as np
 from scipy.special import erf as _erf

@@ -11,7 +11,7 @@ _LIB_NAME = "libtp_layer.so"
 
 TPL_OK, TPL_EINVAL, TPL_EUNSUPPORTED, TPL_EWORKSPACE, TPL_EALIGN, TPL_EHIP = range(6)
 TPL_F32, TPL_BF16 = 0, 1
-TPL_CAUSAL, TPL_ROW_EPILOGUE = 1, 2
+TPL_CAUSAL, TPL_ROW_EPILOGUE, TPL_SIDE_STREAM = 1, 2, 4
 TPL_EPI_NONE, TPL_EPI_GELU, TPL_EPI_DGELU = 0, 1, 2
 TPL_ACT_NONE, TPL_ACT_GELU = 0, 1
 
@@ -88,6 +88,7 @@ def load_library():
         "tp_layer_slice_epilogue_fwd": (ci, [ci, ci, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp]),
         "tp_layer_slice_epilogue_workspace_bytes": (sz, [i64, i64]),
         "tp_layer_slice_epilogue_bwd": (ci, [ci, ci, i64, i64, _vp, _vp, _vp, _vp, _vp, sz, _vp]),
+        "tp_layer_set_option": (ci, [ctypes.c_char_p, ctypes.c_char_p]),
         "tp_layer_profile": (ci, [ci]),
         "tp_layer_profile_read": (ci, [ctypes.POINTER(ctypes.c_float), ci, ctypes.POINTER(ci)]),
         "tp_layer_strerror": (ctypes.c_char_p, [ci]),
@@ -118,8 +119,9 @@ def _stream(stream):
 
 
 def make_desc(hidden, heads, tp_degree, tp_rank, seq, micro_batch, dtype, causal, row_epilogue,
-              head_dim=0, intermediate=0):
-    flags = (TPL_CAUSAL if causal else 0) | (TPL_ROW_EPILOGUE if row_epilogue else 0)
+              head_dim=0, intermediate=0, side_stream=False):
+    flags = ((TPL_CAUSAL if causal else 0) | (TPL_ROW_EPILOGUE if row_epilogue else 0) |
+             (TPL_SIDE_STREAM if side_stream else 0))
     return TpLayerDesc(hidden, heads, head_dim, intermediate, tp_degree, tp_rank, seq, micro_batch,
                        dtype, flags)
 
@@ -278,6 +280,13 @@ def tp_layer_slice_epilogue_bwd(dtype, act, M, N, dout, u, din, dbias, ws, ws_by
                                                     _ptr(ws), (_nbytes(ws) or 0) if ws_bytes is None else ws_bytes,
                                                     _stream(stream))
     return _checked(rc, "tp_layer_slice_epilogue_bwd", check)
+
+
+def tp_layer_set_option(name, value=None, check=True):
+    """Tuning override (see tp_layer.h); value None or "" returns the option to the library's own choice."""
+    v = None if value is None else str(value).encode()
+    rc = load_library().tp_layer_set_option(name.encode(), v)
+    return _checked(rc, f"tp_layer_set_option({name})", check)
 
 
 def tp_layer_profile(enable):

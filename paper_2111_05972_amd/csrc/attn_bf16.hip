@@ -875,14 +875,13 @@ static hipError_t set_lds(K kernel, int bytes) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-// Chunk length in tile steps.  No workspace: strips are never cut.  TPL_ATTN_CHUNK=<n> forces n (0: never cut).
+// Chunk length in tile steps.  No workspace: strips are never cut.  The option attn_chunk = n forces n (0: never cut).
 // Every workgroup costs a few steps' worth of start-up and merge and every cut strip its partials, so strips are
 // cut only where the longest one would otherwise set the duration, and never into chunks of fewer than 8 steps.
 constexpr int NEVER_CUT = 1 << 30;
 static bool forced_chunk(const AttnArgs& a, int* ch) {
     if (!a.ws) { *ch = NEVER_CUT; return true; }
-    if (const char* e = getenv("TPL_ATTN_CHUNK")) {
-        const int v = atoi(e);
+    if (const int v = options().attn_chunk; v >= 0) {
         *ch = v > 0 && v < (1 << 16) ? v : NEVER_CUT;
         return true;
     }

@@ -47,6 +47,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <mutex>
 
 #include "device_math.h"
 #include "kernels.h"
@@ -1349,12 +1350,9 @@ bool gemm_bf16_supported(const GemmArgs& a) {
 // Band height of the tile order.  An XCD's L2 (4 MiB) holds no operand panel for long: what it saves is the reuse
 // among the tiles in flight on the XCD at one time, which walk K together: `inflight` consecutive tiles of the list =
 // h rows x inflight / h columns of the tile grid, needing h A slices and inflight / h B slices per k-step.  The band
-// height minimises h * bm + (inflight / h) * bn.  TPL_GEMM_BAND=<h> forces a height.
+// height minimises h * bm + (inflight / h) * bn.  The option gemm_band = h forces a height.
 static int choose_band(int R, int bm, int bn, int lds_bytes) {
-    if (const char* e = getenv("TPL_GEMM_BAND")) {
-        const int v = atoi(e);
-        if (v > 0) return v;
-    }
+    if (const int v = options().gemm_band; v > 0) return v;
     // 32 compute units per XCD; the kernels with two workgroups per unit were also measured fastest with the band of
     // 32 tiles in flight (4 rows, 0.6 % of the step ahead of 8), so the count is not doubled for them
     (void)lds_bytes;
@@ -1523,14 +1521,14 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj)
     static const int wgs_per_cu[NVARIANTS] = {1, 1, 2, 2, 1, 1, 1, 2};
     static const double us_per_stage[NVARIANTS] = {0.92, 0.758, 0.348, 0.5576, 0.658, 0.70, 0.602, 0.509};
     static const double fixed_us[NVARIANTS] = {12.0, 12.0, 12.0, 12.0, 18.0, 12.5, 18.0, 12.0};
-    const char* e = getenv("TPL_GEMM_TILE");          // tuning / test overrides: one digit; a number
-    int forced_v = (e && e[0] >= '0' && e[0] < '0' + NVARIANTS) ? e[0] - '0' : -1;
-    const char* es = getenv("TPL_GEMM_SHARES");
-    int forced_s = es ? atoi(es) : 0;
-    // TPL_GEMM_FORCE="MxNxK@ab=v[:shares];..." (a, b = 1 if A, B is K-major) overrides the plan of single shapes (tuning inside a whole step)
+    // tuning / test overrides (Options): one variant for every GEMM, a K split, or plans of single shapes
+    const Options& opt = options();
+    int forced_v = (opt.gemm_tile >= 0 && opt.gemm_tile < NVARIANTS) ? opt.gemm_tile : -1;
+    int forced_s = opt.gemm_shares;
+    // gemm_force = "MxNxK@ab=v[:shares];..." (a, b = 1 if A, B is K-major) overrides the plan of single shapes (tuning inside a whole step)
     int forced_shape_v = -1;
-    if (const char* ef = getenv("TPL_GEMM_FORCE")) {
-        const char* q = ef;
+    if (opt.gemm_force[0]) {
+        const char* q = opt.gemm_force;
         while (*q) {
             long long m = 0, n = 0, k = 0; int ak = 0, bk = 0, v = -1, sh = 0, used = 0;
             if (sscanf(q, "%lldx%lldx%lld@%1d%1d=%d%n", &m, &n, &k, &ak, &bk, &v, &used) >= 6) {   // @ab: A, B K-major
@@ -1588,10 +1586,31 @@ static Plan make_plan(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj)
     return best;
 }
 
+// Plans are computed once per (shape, layout) and kept: a launch looks its plan up (a short scan under a mutex), it
+// does not run the planner.  Entries carry the generation of the options they were planned under.
+static Plan plan_for(int64_t M, int64_t N, int64_t K, bool a_kmaj, bool b_kmaj) {
+    struct Entry { int64_t M, N, K; int layout; unsigned gen; Plan plan; };
+    constexpr int CAP = 128;
+    static Entry cache[CAP];
+    static int used = 0, next = 0;
+    static std::mutex mu;
+    const int layout = (a_kmaj ? 1 : 0) | (b_kmaj ? 2 : 0);
+    const unsigned gen = options().generation;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < used; ++i) {
+        const Entry& e = cache[i];
+        if (e.M == M && e.N == N && e.K == K && e.layout == layout && e.gen == gen) return e.plan;
+    }
+    const Plan pl = make_plan(M, N, K, a_kmaj, b_kmaj);
+    const int slot = used < CAP ? used++ : (next++ % CAP);
+    cache[slot] = Entry{M, N, K, layout, gen, pl};
+    return pl;
+}
+
 size_t gemm_bf16_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     size_t need = 0;
     for (int layout = 0; layout < 4; ++layout) {
-        const Plan pl = make_plan(M, N, K, (layout & 1) != 0, (layout & 2) != 0);
+        const Plan pl = plan_for(M, N, K, (layout & 1) != 0, (layout & 2) != 0);
         if (pl.shares > 1) need = std::max(need, (size_t)pl.shares * (size_t)M * (size_t)N * sizeof(float));
     }
     return need;
@@ -1608,7 +1627,7 @@ hipError_t gemm_bf16(const GemmArgs& a) {
     p.epi = a.epi;
     p.tiles_m = p.tiles_n = 0;
     p.band = 8;
-    const Plan pl = make_plan(a.M, a.N, a.K, !a.trans_a, a.trans_b != 0);
+    const Plan pl = plan_for(a.M, a.N, a.K, !a.trans_a, a.trans_b != 0);
     p.nk_total = (int)((a.K + DK - 1) / DK);
     p.nk = pl.nk_share;
     p.partial = nullptr;

@@ -7,6 +7,23 @@
 namespace tpl {
 
 enum Dtype { F32 = 0, BF16 = 1 };
+
+// Tuning overrides of the kernel choices (tests run every tile variant through them; tuning forces single plans).
+// Read from the environment ONCE, when the library is first used (TPL_GEMM_TILE, TPL_GEMM_SHARES, TPL_GEMM_BAND,
+// TPL_GEMM_FORCE, TPL_ATTN_CHUNK); afterwards only tp_layer_set_option changes them.  Nothing on a launch path
+// reads the environment.  `generation` increases with every change: plans cached per shape carry it.
+struct Options {
+    int gemm_tile = -1;        // force one tile variant (0 .. number of variants - 1); -1: the planner chooses
+    int gemm_shares = 0;       // force a K split; 0: the planner chooses
+    int gemm_band = 0;         // force the band height of the tile order; 0: choose_band
+    int attn_chunk = -1;       // force the chunk length of attention strips in 64-row tile steps (0: never cut); -1: unset
+    char gemm_force[1024] = "";   // "MxNxK@ab=v[:shares];..." plans of single shapes (a, b = 1: A, B K-major)
+    unsigned generation = 0;
+};
+const Options& options();
+// name: "gemm_tile", "gemm_shares", "gemm_band", "gemm_force", "attn_chunk"; value null or "": back to unset.
+// Returns false for an unknown name or a value that does not parse.
+bool set_option(const char* name, const char* value);
 enum Epi { EPI_NONE = 0, EPI_GELU = 1, EPI_DGELU = 2 };
 
 // C[M,N] = epi(opA(A) opB(B)); see tp_layer_gemm in tp_layer.h for the meaning of each field.

@@ -4,10 +4,53 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <cstring>
 
 #include "kernels.h"
 
 using namespace tpl;
+
+// ---- tuning overrides (see Options in kernels.h) -------------------------------------------------------------------
+namespace tpl {
+namespace {
+bool parse_int(const char* v, int unset, int lo, int hi, int* out) {
+    if (!v || !*v) { *out = unset; return true; }
+    char* end = nullptr;
+    const long x = strtol(v, &end, 10);
+    if (end == v || *end != 0 || x < lo || x > hi) return false;
+    *out = (int)x;
+    return true;
+}
+Options& mutable_options() {
+    static Options opt = [] {
+        Options o;                                      // the environment is read here, once per process
+        parse_int(getenv("TPL_GEMM_TILE"), -1, 0, 63, &o.gemm_tile);
+        parse_int(getenv("TPL_GEMM_SHARES"), 0, 0, 64, &o.gemm_shares);
+        parse_int(getenv("TPL_GEMM_BAND"), 0, 0, 1 << 20, &o.gemm_band);
+        parse_int(getenv("TPL_ATTN_CHUNK"), -1, 0, 1 << 16, &o.attn_chunk);
+        if (const char* f = getenv("TPL_GEMM_FORCE")) { strncpy(o.gemm_force, f, sizeof(o.gemm_force) - 1); }
+        return o;
+    }();
+    return opt;
+}
+}  // namespace
+const Options& options() { return mutable_options(); }
+bool set_option(const char* name, const char* value) {
+    if (!name) return false;
+    Options& o = mutable_options();
+    bool ok = false;
+    if (!strcmp(name, "gemm_tile")) ok = parse_int(value, -1, 0, 63, &o.gemm_tile);
+    else if (!strcmp(name, "gemm_shares")) ok = parse_int(value, 0, 0, 64, &o.gemm_shares);
+    else if (!strcmp(name, "gemm_band")) ok = parse_int(value, 0, 0, 1 << 20, &o.gemm_band);
+    else if (!strcmp(name, "attn_chunk")) ok = parse_int(value, -1, 0, 1 << 16, &o.attn_chunk);
+    else if (!strcmp(name, "gemm_force")) {
+        const char* v = value ? value : "";
+        if (strlen(v) < sizeof(o.gemm_force)) { strcpy(o.gemm_force, v); ok = true; }
+    }
+    if (ok) ++o.generation;
+    return ok;
+}
+}  // namespace tpl
 
 namespace {
 
@@ -19,7 +62,7 @@ struct Dims {
     int64_t H, nh, dh, I, T, r, S, B, M, nl, Hl, Il;
     int dtype;
     size_t esz;
-    bool causal, row_epi;
+    bool causal, row_epi, side_stream;
 };
 
 int resolve(const tp_layer_desc* d, Dims* o) {
@@ -28,7 +71,7 @@ int resolve(const tp_layer_desc* d, Dims* o) {
         return TPL_EINVAL;
     if (d->head_dim < 0 || d->intermediate < 0) return TPL_EINVAL;
     if (d->dtype != TPL_F32 && d->dtype != TPL_BF16) return TPL_EINVAL;
-    if (d->flags & ~(uint32_t)(TPL_CAUSAL | TPL_ROW_EPILOGUE)) return TPL_EINVAL;
+    if (d->flags & ~(uint32_t)(TPL_CAUSAL | TPL_ROW_EPILOGUE | TPL_SIDE_STREAM)) return TPL_EINVAL;
     if (d->tp_rank < 0 || d->tp_rank >= d->tp_degree) return TPL_EINVAL;
     Dims x;
     x.H = d->hidden; x.nh = d->heads; x.T = d->tp_degree; x.r = d->tp_rank;
@@ -41,6 +84,7 @@ int resolve(const tp_layer_desc* d, Dims* o) {
     x.M = x.B * x.S; x.nl = x.nh / x.T; x.Hl = x.nl * x.dh; x.Il = x.I / x.T;
     x.dtype = d->dtype; x.esz = d->dtype == TPL_F32 ? 4 : 2;
     x.causal = d->flags & TPL_CAUSAL; x.row_epi = d->flags & TPL_ROW_EPILOGUE;
+    x.side_stream = d->flags & TPL_SIDE_STREAM;
     if (x.M > (int64_t)1 << 24 || x.H > (int64_t)1 << 20 || x.I > (int64_t)1 << 24) return TPL_EUNSUPPORTED;
     if (x.dh > 256) return TPL_EUNSUPPORTED;
     // 16-byte rows for every matrix the kernels touch
@@ -122,13 +166,13 @@ struct GemmProfile {
 } g_prof;
 
 // The attention block and the MLP block of one pass share no tensor (each has its own input, output and
-// gradients), so they are enqueued as two chains: the attention chain on the caller's stream and the MLP chain
-// on a second stream that the library creates once per device (default priority, non-blocking).  The second
-// stream is forked from the caller's stream and joined back to it with events, so the caller sees one pass on
-// its stream and the host never waits.  What the overlap buys: tiles of one chain fill the compute units the
-// other leaves idle (a GEMM whose tile count is below the number of compute units, the attention kernels,
-// the start and end of every kernel).  With per-GEMM timing on (tp_layer_profile) or TPL_SINGLE_STREAM=1 in
-// the environment everything runs on the caller's stream in the order written.
+// gradients).  By default both are enqueued on the caller's stream, in the order written.  With TPL_SIDE_STREAM in
+// the descriptor's flags they are enqueued as two chains: the attention chain on the caller's stream and the MLP
+// chain on a second stream that the library creates once per device (default priority, non-blocking).  The second
+// stream is forked from the caller's stream and joined back to it with events, so the caller sees one pass on its
+// stream and the host never waits.  What the overlap can buy: tiles of one chain fill the compute units the other
+// leaves idle (a GEMM whose tile count is below the number of compute units, the attention kernels, the start and
+// end of every kernel).  Per-GEMM timing (tp_layer_profile) keeps everything on the caller's stream.
 struct SideStream {
     hipStream_t stream = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
@@ -139,9 +183,8 @@ SideStream g_side[MAX_DEVICES];
 
 // Returns the stream for the second chain, already waiting for everything enqueued on s so far; s itself when
 // the second stream is not used.
-hipStream_t side_fork(hipStream_t s) {
-    static const bool single = [] { const char* e = getenv("TPL_SINGLE_STREAM"); return e && e[0] == '1'; }();
-    if (single || g_prof.on) return s;
+hipStream_t side_fork(hipStream_t s, bool wanted) {
+    if (!wanted || g_prof.on) return s;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return s;
     SideStream& ss = g_side[dev];
@@ -163,6 +206,14 @@ int side_join(hipStream_t s, hipStream_t s2) {
     if (hipEventRecord(ss.join, s2) != hipSuccess || hipStreamWaitEvent(s, ss.join, 0) != hipSuccess) return TPL_EHIP;
     return TPL_OK;
 }
+// A pass that fails after the fork still joins: the caller's stream must not run ahead of work already enqueued
+// on the second stream that touches the caller's buffers.
+struct SideJoin {
+    hipStream_t s, s2;
+    bool done = false;
+    int finish() { done = true; return side_join(s, s2); }
+    ~SideJoin() { if (!done) side_join(s, s2); }
+};
 
 int run_gemm(GemmArgs& g) {
     hipError_t e;
@@ -213,7 +264,8 @@ int fwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
     float* lse = (float*)(sv + L.lse);
     // each chain has its own half of the GEMM scratch
     const size_t half = fwd_gemm_ws(x);
-    hipStream_t s2 = side_fork(s);
+    hipStream_t s2 = side_fork(s, x.side_stream);
+    SideJoin sj{s, s2};
     GemmScratch sc{ws, half, s}, sc2{(char*)ws + half, half, s2};
 
     // MLP block (second chain): column-parallel up-projection + GeLU, row-parallel down-projection
@@ -240,9 +292,93 @@ int fwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
         if (x.row_epi) { g3.bias = p->b_o; g3.resid = x_attn; }
         if ((rc = run_gemm(g3))) return rc;
     }
-    return side_join(s, s2);
+    return sj.finish();
 }
 
+// Argument checks shared by the entry points: NULL pointers, then alignment.  `row_parallel`: the forward pass
+// runs its two row-parallel GEMMs (they need b_o, b_dn on the epilogue rank); the recomputation of checkpoint
+// mode does not.
+int fwd_check(const Dims& x, const tp_layer_params* p, const void* x_attn, const void* x_mlp, const void* ws,
+              bool row_parallel) {
+    if (!p || !x_attn || !x_mlp || !ws) return TPL_EINVAL;
+    if (!p->w_qkv || !p->b_qkv || !p->w_o || !p->w_up || !p->b_up || !p->w_dn) return TPL_EINVAL;
+    if (row_parallel && x.row_epi && (!p->b_o || !p->b_dn)) return TPL_EINVAL;
+    const void* ptrs[] = {x_attn, x_mlp, ws, p->w_qkv, p->b_qkv, p->w_o, p->b_o, p->w_up, p->b_up, p->w_dn, p->b_dn};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    return TPL_OK;
+}
+
+int bwd_check(const Dims& x, const tp_layer_params* p, const void* x_attn, const void* x_mlp, const void* dy_attn,
+              const void* dy_mlp, const tp_layer_grads* gr, const void* dx_attn, const void* dx_mlp, const void* ws) {
+    if (!p || !gr || !x_attn || !x_mlp || !dy_attn || !dy_mlp || !dx_attn || !dx_mlp || !ws) return TPL_EINVAL;
+    if (!p->w_qkv || !p->w_o || !p->w_up || !p->w_dn) return TPL_EINVAL;
+    if (!gr->dw_qkv || !gr->db_qkv || !gr->dw_o || !gr->dw_up || !gr->db_up || !gr->dw_dn) return TPL_EINVAL;
+    if (x.row_epi && (!gr->db_o || !gr->db_dn)) return TPL_EINVAL;
+    const void* ptrs[] = {x_attn, x_mlp, dy_attn, dy_mlp, dx_attn, dx_mlp, ws, p->w_qkv, p->w_o,
+                          p->w_up, p->w_dn, gr->dw_qkv, gr->db_qkv, gr->dw_o, gr->db_o, gr->dw_up,
+                          gr->db_up, gr->dw_dn, gr->db_dn};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    return TPL_OK;
+}
+
+// Backward kernels in order (arguments already checked, ws large enough).
+int bwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const void* x_mlp, const void* dy_attn,
+             const void* dy_mlp, const void* saved, const tp_layer_grads* gr, void* dx_attn, void* dx_mlp, void* ws,
+             hipStream_t s) {
+    int rc;
+    BwdWs W;
+    bwd_layout(x, &W);
+    tp_layer_saved_layout L;
+    saved_layout(x, &L);
+    const char* sv = (const char*)saved;
+    const void *qkv = sv + L.qkv, *o = sv + L.o, *u = sv + L.u, *g = sv + L.g;
+    const float* lse = (const float*)(sv + L.lse);
+    char* w = (char*)ws;
+    void *du = w + W.du, *d_o = w + W.d_o, *dqkv = w + W.dqkv;
+    float *dsum = (float*)(w + W.dsum), *cs = (float*)(w + W.colsum), *cs2 = (float*)(w + W.colsum2);
+    hipStream_t s2 = side_fork(s, x.side_stream);
+    SideJoin sj{s, s2};
+    GemmScratch sc{w + W.gemm, W.gemm_each, s}, sc2{w + W.gemm2, W.gemm_each, s2};
+
+    // MLP block (second chain).  dU = (dy_m W_dn^T) * gelu'(U) in one GEMM epilogue.
+    GemmArgs b5 = mk(x, 0, 1, x.M, x.Il, x.H, dy_mlp, p->w_dn, du, sc2);
+    b5.aux = const_cast<void*>(u); b5.epi = EPI_DGELU;
+    if ((rc = run_gemm(b5))) return rc;
+    GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, sc2);
+    w5.c_streaming = true;                   // the weight gradient is not read again in this pass
+    if ((rc = run_gemm(w5))) return rc;
+    GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, sc2);
+    w4.c_streaming = true;
+    if ((rc = run_gemm(w4))) return rc;
+    if (colsum(x.dtype, x.M, x.Il, du, gr->db_up, cs2, s2) != hipSuccess) return TPL_EHIP;
+    GemmArgs d4 = mk(x, 0, 1, x.M, x.H, x.Il, du, p->w_up, dx_mlp, sc2);
+    if (x.row_epi) d4.resid = dy_mlp;
+    if ((rc = run_gemm(d4))) return rc;
+    if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_mlp, gr->db_dn, cs2, s2) != hipSuccess) return TPL_EHIP;
+
+    // attention block
+    GemmArgs d3 = mk(x, 0, 1, x.M, x.Hl, x.H, dy_attn, p->w_o, d_o, sc);
+    if ((rc = run_gemm(d3))) return rc;
+    GemmArgs w3 = mk(x, 1, 0, x.Hl, x.H, x.M, o, dy_attn, gr->dw_o, sc);
+    w3.c_streaming = true;
+    if ((rc = run_gemm(w3))) return rc;
+    if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_attn, gr->db_o, cs, s) != hipSuccess) return TPL_EHIP;
+    AttnArgs at{};
+    at.dtype = x.dtype; at.B = (int)x.B; at.S = (int)x.S; at.nl = (int)x.nl; at.dh = (int)x.dh;
+    at.causal = x.causal; at.qkv = qkv; at.o = const_cast<void*>(o); at.lse = const_cast<float*>(lse);
+    at.d_o = d_o; at.dqkv = dqkv; at.dsum = dsum; at.stream = s;
+    at.ws_bytes = W.attn_bytes;
+    at.ws = W.attn_bytes ? w + W.attn : nullptr;
+    if ((rc = run_attn(at, true))) return rc;
+    GemmArgs w1 = mk(x, 1, 0, x.H, 3 * x.Hl, x.M, x_attn, dqkv, gr->dw_qkv, sc);
+    w1.c_streaming = true;
+    if ((rc = run_gemm(w1))) return rc;
+    if (colsum(x.dtype, x.M, 3 * x.Hl, dqkv, gr->db_qkv, cs, s) != hipSuccess) return TPL_EHIP;
+    GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, sc);
+    if (x.row_epi) d1.resid = dy_attn;
+    if ((rc = run_gemm(d1))) return rc;
+    return sj.finish();
+}
 }  // namespace
 
 extern "C" {
@@ -281,13 +417,10 @@ int tp_layer_fwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     Dims x;
     int rc = resolve(desc, &x);
     if (rc != TPL_OK) return rc;
-    if (!p || !x_attn || !x_mlp || !y_attn || !y_mlp || !saved || !ws) return TPL_EINVAL;
-    if (!p->w_qkv || !p->b_qkv || !p->w_o || !p->w_up || !p->b_up || !p->w_dn) return TPL_EINVAL;
-    if (x.row_epi && (!p->b_o || !p->b_dn)) return TPL_EINVAL;
-    const void* ptrs[] = {x_attn, x_mlp, y_attn, y_mlp, saved, ws, p->w_qkv, p->b_qkv, p->w_o,
-                          p->b_o, p->w_up, p->b_up, p->w_dn, p->b_dn};
-    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
-    if (ws_bytes < 2 * fwd_gemm_ws(x)) return TPL_EWORKSPACE;
+    if ((rc = fwd_check(x, p, x_attn, x_mlp, ws, true))) return rc;
+    if (!y_attn || !y_mlp || !saved) return TPL_EINVAL;
+    if (misaligned(y_attn) || misaligned(y_mlp) || misaligned(saved)) return TPL_EALIGN;
+    if (ws_bytes < fwd_ws_total(x)) return TPL_EWORKSPACE;
     return fwd_impl(x, p, x_attn, x_mlp, y_attn, y_mlp, saved, ws, ws_bytes, (hipStream_t)hip_stream, true);
 }
 
@@ -298,68 +431,13 @@ int tp_layer_bwd(const tp_layer_desc* desc, const tp_layer_params* p, const void
     Dims x;
     int rc = resolve(desc, &x);
     if (rc != TPL_OK) return rc;
-    if (!p || !gr || !x_attn || !x_mlp || !dy_attn || !dy_mlp || !saved || !dx_attn || !dx_mlp || !ws)
-        return TPL_EINVAL;
-    if (!p->w_qkv || !p->w_o || !p->w_up || !p->w_dn) return TPL_EINVAL;
-    if (!gr->dw_qkv || !gr->db_qkv || !gr->dw_o || !gr->dw_up || !gr->db_up || !gr->dw_dn) return TPL_EINVAL;
-    if (x.row_epi && (!gr->db_o || !gr->db_dn)) return TPL_EINVAL;
-    const void* ptrs[] = {x_attn, x_mlp, dy_attn, dy_mlp, saved, dx_attn, dx_mlp, ws, p->w_qkv, p->w_o,
-                          p->w_up, p->w_dn, gr->dw_qkv, gr->db_qkv, gr->dw_o, gr->db_o, gr->dw_up,
-                          gr->db_up, gr->dw_dn, gr->db_dn};
-    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    if ((rc = bwd_check(x, p, x_attn, x_mlp, dy_attn, dy_mlp, gr, dx_attn, dx_mlp, ws))) return rc;
+    if (!saved) return TPL_EINVAL;
+    if (misaligned(saved)) return TPL_EALIGN;
     BwdWs W;
     bwd_layout(x, &W);
     if (ws_bytes < W.total) return TPL_EWORKSPACE;
-    hipStream_t s = (hipStream_t)hip_stream;
-    tp_layer_saved_layout L;
-    saved_layout(x, &L);
-    const char* sv = (const char*)saved;
-    const void *qkv = sv + L.qkv, *o = sv + L.o, *u = sv + L.u, *g = sv + L.g;
-    const float* lse = (const float*)(sv + L.lse);
-    char* w = (char*)ws;
-    void *du = w + W.du, *d_o = w + W.d_o, *dqkv = w + W.dqkv;
-    float *dsum = (float*)(w + W.dsum), *cs = (float*)(w + W.colsum), *cs2 = (float*)(w + W.colsum2);
-    hipStream_t s2 = side_fork(s);
-    GemmScratch sc{w + W.gemm, W.gemm_each, s}, sc2{w + W.gemm2, W.gemm_each, s2};
-
-    // MLP block (second chain).  dU = (dy_m W_dn^T) * gelu'(U) in one GEMM epilogue.
-    GemmArgs b5 = mk(x, 0, 1, x.M, x.Il, x.H, dy_mlp, p->w_dn, du, sc2);
-    b5.aux = const_cast<void*>(u); b5.epi = EPI_DGELU;
-    if ((rc = run_gemm(b5))) return rc;
-    GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, sc2);
-    w5.c_streaming = true;                   // the weight gradient is not read again in this pass
-    if ((rc = run_gemm(w5))) return rc;
-    GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, sc2);
-    w4.c_streaming = true;                   // the weight gradient is not read again in this pass
-    if ((rc = run_gemm(w4))) return rc;
-    if (colsum(x.dtype, x.M, x.Il, du, gr->db_up, cs2, s2) != hipSuccess) return TPL_EHIP;
-    GemmArgs d4 = mk(x, 0, 1, x.M, x.H, x.Il, du, p->w_up, dx_mlp, sc2);
-    if (x.row_epi) d4.resid = dy_mlp;
-    if ((rc = run_gemm(d4))) return rc;
-    if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_mlp, gr->db_dn, cs2, s2) != hipSuccess) return TPL_EHIP;
-
-    // attention block
-    GemmArgs d3 = mk(x, 0, 1, x.M, x.Hl, x.H, dy_attn, p->w_o, d_o, sc);
-    if ((rc = run_gemm(d3))) return rc;
-    GemmArgs w3 = mk(x, 1, 0, x.Hl, x.H, x.M, o, dy_attn, gr->dw_o, sc);
-    w3.c_streaming = true;                   // the weight gradient is not read again in this pass
-    if ((rc = run_gemm(w3))) return rc;
-    if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_attn, gr->db_o, cs, s) != hipSuccess) return TPL_EHIP;
-    AttnArgs at{};
-    at.dtype = x.dtype; at.B = (int)x.B; at.S = (int)x.S; at.nl = (int)x.nl; at.dh = (int)x.dh;
-    at.causal = x.causal; at.qkv = qkv; at.o = const_cast<void*>(o); at.lse = const_cast<float*>(lse);
-    at.d_o = d_o; at.dqkv = dqkv; at.dsum = dsum; at.stream = s;
-    at.ws_bytes = W.attn_bytes;
-    at.ws = W.attn_bytes ? w + W.attn : nullptr;
-    if ((rc = run_attn(at, true))) return rc;
-    GemmArgs w1 = mk(x, 1, 0, x.H, 3 * x.Hl, x.M, x_attn, dqkv, gr->dw_qkv, sc);
-    w1.c_streaming = true;                   // the weight gradient is not read again in this pass
-    if ((rc = run_gemm(w1))) return rc;
-    if (colsum(x.dtype, x.M, 3 * x.Hl, dqkv, gr->db_qkv, cs, s) != hipSuccess) return TPL_EHIP;
-    GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, sc);
-    if (x.row_epi) d1.resid = dy_attn;
-    if ((rc = run_gemm(d1))) return rc;
-    return side_join(s, s2);
+    return bwd_impl(x, p, x_attn, x_mlp, dy_attn, dy_mlp, saved, gr, dx_attn, dx_mlp, ws, (hipStream_t)hip_stream);
 }
 
 size_t tp_layer_workspace_bytes_recompute(const tp_layer_desc* desc) {
@@ -379,10 +457,9 @@ int tp_layer_bwd_recompute(const tp_layer_desc* desc, const tp_layer_params* p, 
     Dims x;
     int rc = resolve(desc, &x);
     if (rc != TPL_OK) return rc;
-    if (!p || !x_attn || !x_mlp || !ws) return TPL_EINVAL;
-    if (!p->w_qkv || !p->b_qkv || !p->w_o || !p->w_up || !p->b_up || !p->w_dn) return TPL_EINVAL;
-    const void* ptrs[] = {x_attn, x_mlp, ws, p->w_qkv, p->b_qkv, p->w_o, p->w_up, p->b_up, p->w_dn};
-    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    // everything either pass needs is checked before the recomputed forward is enqueued
+    if ((rc = fwd_check(x, p, x_attn, x_mlp, ws, false))) return rc;
+    if ((rc = bwd_check(x, p, x_attn, x_mlp, dy_attn, dy_mlp, gr, dx_attn, dx_mlp, ws))) return rc;
     if (ws_bytes < tp_layer_workspace_bytes_recompute(desc)) return TPL_EWORKSPACE;
     tp_layer_saved_layout L;
     saved_layout(x, &L);
@@ -392,8 +469,7 @@ int tp_layer_bwd_recompute(const tp_layer_desc* desc, const tp_layer_params* p, 
     // recompute QKV, O, LSE, U, G from the block inputs, then the ordinary backward
     rc = fwd_impl(x, p, x_attn, x_mlp, nullptr, nullptr, saved, rest, rest_bytes, (hipStream_t)hip_stream, false);
     if (rc != TPL_OK) return rc;
-    return tp_layer_bwd(desc, p, x_attn, x_mlp, dy_attn, dy_mlp, saved, gr, dx_attn, dx_mlp, rest, rest_bytes,
-                        hip_stream);
+    return bwd_impl(x, p, x_attn, x_mlp, dy_attn, dy_mlp, saved, gr, dx_attn, dx_mlp, rest, (hipStream_t)hip_stream);
 }
 
 static int ln_check(int dtype, int64_t M, int64_t H) {
@@ -612,6 +688,10 @@ int tp_layer_attn_bwd(int dtype, int B, int S, int nl, int dh, int causal, const
     a.dqkv = dqkv; a.dsum = d_scratch; a.ws = ws; a.ws_bytes = ws_bytes; a.own_chunking = 1;
     a.stream = (hipStream_t)hip_stream;
     return run_attn(a, true);
+}
+
+int tp_layer_set_option(const char* name, const char* value) {
+    return set_option(name, value) ? TPL_OK : TPL_EINVAL;
 }
 
 int tp_layer_profile(int enable) {

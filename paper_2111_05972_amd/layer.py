@@ -42,9 +42,9 @@ class TpLayer:
     """One rank's layer shard: owns saved/workspace buffers and calls tp_layer_fwd / tp_layer_bwd."""
 
     def __init__(self, hidden, heads, tp_degree, tp_rank, seq, micro_batch, dtype, causal,
-                 row_epilogue, head_dim=0, intermediate=0, device="cuda"):
+                 row_epilogue, head_dim=0, intermediate=0, device="cuda", side_stream=False):
         self.desc = B.make_desc(hidden, heads, tp_degree, tp_rank, seq, micro_batch, dtype, causal,
-                                row_epilogue, head_dim, intermediate)
+                                row_epilogue, head_dim, intermediate, side_stream)
         rc = B.tp_layer_validate(self.desc)
         if rc != B.TPL_OK:
             raise B.TpLayerError(rc, "tp_layer_validate")

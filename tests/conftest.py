@@ -28,3 +28,24 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+class _Tune:
+    """Sets the library's tuning overrides (tp_layer_set_option) for one test; all are cleared afterwards."""
+    NAMES = ("gemm_tile", "gemm_shares", "gemm_band", "gemm_force", "attn_chunk")
+
+    def set(self, name, value):
+        import paper_2111_05972_amd as pkg
+        pkg.tp_layer_set_option(name, value)
+
+    def clear(self):
+        for n in self.NAMES:
+            self.set(n, None)
+
+
+@pytest.fixture
+def tune():
+    t = _Tune()
+    t.clear()
+    yield t
+    t.clear()

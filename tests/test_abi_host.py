@@ -70,6 +70,8 @@ def test_invalid_descriptors():
     d = _desc(cfg)
     d.flags = 8
     assert pkg.tp_layer_validate(d) == pkg.TPL_EINVAL
+    d.flags = pkg.TPL_CAUSAL | pkg.TPL_SIDE_STREAM          # scheduling flag: a valid descriptor
+    assert pkg.tp_layer_validate(d) == pkg.TPL_OK
     assert pkg.tp_layer_validate(None) == pkg.TPL_EINVAL
     # valid layers without a kernel
     assert pkg.tp_layer_validate(_desc(cfg, hidden=1020, heads=4, head_dim=255, intermediate=4080)) == pkg.TPL_EUNSUPPORTED
@@ -110,12 +112,61 @@ def test_calls_are_rejected_before_any_launch():
     assert "workspace" in pkg.tp_layer_strerror(pkg.TPL_EWORKSPACE)
 
 
-def test_attention_workspace_follows_the_chunk_length(monkeypatch):
+def test_forward_workspace_check_covers_the_attention_partials(tune):
+    """With a forced attention chunk length the forward pass keeps float partials behind the two GEMM scratch
+    halves: the size check of tp_layer_fwd is the size tp_layer_workspace_bytes reports, not the GEMM part alone."""
+    cfg = synthetic.CONFIGS[4]
+    d = _desc(cfg)
+    ok, big = 0x1000, 1 << 40
+    P = {k: ok for k in ("w_qkv", "b_qkv", "w_o", "b_o", "w_up", "b_up", "w_dn", "b_dn")}
+    plain = pkg.tp_layer_workspace_bytes(d, 0)
+    tune.set("attn_chunk", "2")
+    forced = pkg.tp_layer_workspace_bytes(d, 0)
+    assert forced > plain                                    # the partials of the cut strips
+    f = lambda n: pkg.tp_layer_fwd(d, P, ok, ok, ok, ok, ok, ok, ws_bytes=n, check=False)   # noqa: E731
+    assert f(plain) == pkg.TPL_EWORKSPACE                    # a buffer of the old size would be overrun
+    assert f(forced - 1) == pkg.TPL_EWORKSPACE
+
+
+def test_recompute_backward_validates_everything_before_enqueueing():
+    """tp_layer_bwd_recompute runs a forward first: every argument of the backward part is checked before it."""
+    cfg = synthetic.CONFIGS[3]                               # row epilogue on
+    d = _desc(cfg)
+    ok, big = 0x1000, 1 << 40
+    P = {k: ok for k in ("w_qkv", "b_qkv", "w_o", "b_o", "w_up", "b_up", "w_dn", "b_dn")}
+    G = {"d" + k: ok for k in P}
+
+    def r(params=P, dy=ok, grads=G, dx=ok, ws=ok, ws_bytes=big):
+        return pkg.tp_layer_bwd_recompute(d, params, ok, ok, dy, ok, grads, dx, ok, ws, ws_bytes=ws_bytes, check=False)
+    assert r(dy=None) == pkg.TPL_EINVAL
+    assert r(dx=None) == pkg.TPL_EINVAL
+    assert r(grads={**G, "dw_qkv": None}) == pkg.TPL_EINVAL
+    assert r(grads={**G, "db_o": None}) == pkg.TPL_EINVAL    # written on the epilogue rank
+    assert r(grads={**G, "db_up": ok + 4}) == pkg.TPL_EALIGN
+    assert r(dy=ok + 8) == pkg.TPL_EALIGN
+    assert r(params={**P, "b_up": None}) == pkg.TPL_EINVAL   # the recomputed forward needs it
+    assert r(ws_bytes=pkg.tp_layer_workspace_bytes_recompute(d) - 1) == pkg.TPL_EWORKSPACE
+
+
+def test_options_are_set_through_the_abi_not_the_environment(tune, monkeypatch):
+    ws = lambda: pkg.tp_layer_gemm_workspace_bytes(pkg.TPL_BF16, 512, 512, 4096)   # noqa: E731
+    base = ws()
+    monkeypatch.setenv("TPL_GEMM_SHARES", "3")               # the environment is read once, at load: no effect now
+    assert ws() == base
+    tune.set("gemm_shares", "3")
+    assert ws() >= 3 * 512 * 512 * 4
+    tune.set("gemm_shares", None)
+    assert ws() == base
+    assert pkg.tp_layer_set_option("no_such_option", "1", check=False) == pkg.TPL_EINVAL
+    assert pkg.tp_layer_set_option("gemm_tile", "x", check=False) == pkg.TPL_EINVAL
+
+
+def test_attention_workspace_follows_the_chunk_length(tune):
     """Partials of the cut strips: causal S = 300 has query strips of 2, 4, 5 tile steps and key strips of 5, 3, 1;
     with chunks of 2 steps that is 1 + 2 + 3 slots on the query side and 3 + 2 + 1 on the key side."""
     import paper_2111_05972_amd as pkg
     B, S, nl, dh = 2, 300, 3, 128
-    monkeypatch.setenv("TPL_ATTN_CHUNK", "2")
+    tune.set("attn_chunk", "2")
     up = lambda n: (n + 255) // 256 * 256      # noqa: E731
     assert pkg.tp_layer_attn_workspace_bytes(pkg.TPL_BF16, B, S, nl, dh, 1, 0) == up(6 * B * nl * 128 * (dh + 2) * 4)
     assert pkg.tp_layer_attn_workspace_bytes(pkg.TPL_BF16, B, S, nl, dh, 1, 1) == up(6 * B * nl * 128 * 3 * dh * 4)
@@ -125,7 +176,7 @@ def test_attention_workspace_follows_the_chunk_length(monkeypatch):
                                  check=False) == pkg.TPL_EWORKSPACE
     assert pkg.tp_layer_attn_bwd(pkg.TPL_BF16, B, S, nl, dh, 1, ok, ok, ok, ok, ok, ok, ws=ok, ws_bytes=1024,
                                  check=False) == pkg.TPL_EWORKSPACE
-    monkeypatch.setenv("TPL_ATTN_CHUNK", "0")
+    tune.set("attn_chunk", "0")
     assert pkg.tp_layer_attn_workspace_bytes(pkg.TPL_BF16, B, S, nl, dh, 1, 1) == 0
 
 
@@ -139,20 +190,20 @@ def test_package_sharding_helper_matches_oracle_rule():
             assert np.array_equal(np.asarray(a[k]), b[k]), k
 
 
-def test_gemm_workspace_follows_the_k_share_plan(monkeypatch):
+def test_gemm_workspace_follows_the_k_share_plan(tune):
     """Host-side planning only: a GEMM with few tiles and a long K asks for float partial sums of whole shares,
     a GEMM that fills the chip asks for the minimum, and a forced share count is honoured."""
-    monkeypatch.delenv("TPL_GEMM_TILE", raising=False)
-    monkeypatch.delenv("TPL_GEMM_SHARES", raising=False)
+    tune.set("gemm_tile", None)
+    tune.set("gemm_shares", None)
     ws = lambda M, N, K: pkg.tp_layer_gemm_workspace_bytes(pkg.TPL_BF16, M, N, K)   # noqa: E731
     few = ws(2048, 1536, 12288)                      # 64 tiles of 256 x 192 on 256 compute units
     assert few % (2048 * 1536 * 4) == 0 and 2 <= few // (2048 * 1536 * 4) <= 16
     assert ws(2048, 12288, 6144) == 256              # fills the chip: no split, minimum size
     assert ws(2048, 1536, 1024) == 256               # K too short to share
-    monkeypatch.setenv("TPL_GEMM_SHARES", "3")
+    tune.set("gemm_shares", "3")
     assert ws(512, 512, 4096) >= 3 * 512 * 512 * 4
     # the layer's workspace covers the split GEMMs of both chains of a pass
-    monkeypatch.delenv("TPL_GEMM_SHARES", raising=False)
+    tune.set("gemm_shares", None)
     cfg = synthetic.get_config(5)
     d = pkg.make_desc(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, pkg.TPL_BF16,
                       cfg.causal, cfg.row_epilogue, cfg.head_dim, cfg.intermediate)

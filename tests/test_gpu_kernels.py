@@ -23,16 +23,13 @@ GEMM_SHAPES = [(256, 256, 64), (520, 264, 136), (1000, 776, 2056), (64, 1536, 40
                (2048, 1536, 3080), (4104, 4360, 520)]
 
 
-# bf16 runs once per tile variant of the MFMA kernel (forced through TPL_GEMM_TILE) and once with the
+# bf16 runs once per tile variant of the MFMA kernel (forced through the option gemm_tile) and once with the
 # library's own choice; float has a single kernel.
-def _check_gemms(dtype, tile, shares, ta, tb, epi, shapes, monkeypatch):
+def _check_gemms(dtype, tile, shares, ta, tb, epi, shapes, tune):
     import torch
     import paper_2111_05972_amd as pkg
-    for name, val in (("TPL_GEMM_TILE", tile), ("TPL_GEMM_SHARES", shares)):
-        if val is None:
-            monkeypatch.delenv(name, raising=False)
-        else:
-            monkeypatch.setenv(name, val)
+    for name, val in (("gemm_tile", tile), ("gemm_shares", shares)):
+        tune.set(name, val)
     dt = pkg.TPL_BF16 if dtype == "bf16" else pkg.TPL_F32
     tol = 2e-2 if dtype == "bf16" else 1e-4
     for si, (M, N, K) in enumerate(shapes):
@@ -77,8 +74,8 @@ def _check_gemms(dtype, tile, shares, ta, tb, epi, shapes, monkeypatch):
 @pytest.mark.parametrize("dtype,tile", [("bf16", None), ("bf16", "0"), ("bf16", "1"), ("bf16", "2"), ("bf16", "3"), ("bf16", "4"), ("bf16", "5"), ("bf16", "6"), ("bf16", "7"), ("f32", None)])
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("epi", ["none", "bias", "bias_resid", "gelu", "dgelu"])
-def test_gemm_variants(dtype, tile, ta, tb, epi, monkeypatch):
-    _check_gemms(dtype, tile, None, ta, tb, epi, GEMM_SHAPES, monkeypatch)
+def test_gemm_variants(dtype, tile, ta, tb, epi, tune):
+    _check_gemms(dtype, tile, None, ta, tb, epi, GEMM_SHAPES, tune)
 
 
 # K cut into shares (one workgroup per tile and share, partial sums added in share order by a second kernel):
@@ -91,30 +88,30 @@ SPLIT_SHAPES = [(256, 192, 520), (520, 264, 1096), (264, 512, 72), (8, 8, 8), (1
 @pytest.mark.parametrize("shares", ["2", "5"])
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("epi", ["bias_resid", "gelu", "dgelu"])
-def test_gemm_k_shares(tile, shares, ta, tb, epi, monkeypatch):
-    _check_gemms("bf16", tile, shares, ta, tb, epi, SPLIT_SHAPES, monkeypatch)
+def test_gemm_k_shares(tile, shares, ta, tb, epi, tune):
+    _check_gemms("bf16", tile, shares, ta, tb, epi, SPLIT_SHAPES, tune)
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 0), (0, 1), (1, 0)])
-def test_gemm_k_shares_own_choice(ta, tb, monkeypatch):
+def test_gemm_k_shares_own_choice(ta, tb, tune):
     import paper_2111_05972_amd as pkg
-    monkeypatch.delenv("TPL_GEMM_TILE", raising=False)
-    monkeypatch.delenv("TPL_GEMM_SHARES", raising=False)
+    tune.set("gemm_tile", None)
+    tune.set("gemm_shares", None)
     M, N, K = 512, 384, 8200
     assert pkg.tp_layer_gemm_workspace_bytes(pkg.TPL_BF16, M, N, K) >= 2 * M * N * 4     # it does split
-    _check_gemms("bf16", None, None, ta, tb, "bias_resid", [(M, N, K)], monkeypatch)
+    _check_gemms("bf16", None, None, ta, tb, "bias_resid", [(M, N, K)], tune)
 
 
 ATTN_CASES = [(2, 128, 2, 64), (1, 300, 3, 128), (3, 77, 2, 32), (1, 1, 4, 64), (2, 513, 1, 64), (1, 1024, 2, 128)]
 
 
 @pytest.mark.parametrize("causal", [True, False])
-def test_attention_long_sequence_own_chunk_length(causal, monkeypatch):
+def test_attention_long_sequence_own_chunk_length(causal, tune):
     """S = 4096 on two heads: far fewer strips than compute units, so with a workspace the library cuts them by
     its own rule (several chunks per strip, also without a mask); forward and backward against the oracle."""
     import torch
     import paper_2111_05972_amd as pkg
-    monkeypatch.delenv("TPL_ATTN_CHUNK", raising=False)
+    tune.set("attn_chunk", None)
     B, S, nl, dh, dt, tol = 1, 4096, 2, 128, pkg.TPL_BF16, 2e-2
     print(f"\n[attn] long S causal={causal} B={B} S={S} nl={nl} dh={dh}", flush=True)
     nf, nb = (pkg.tp_layer_attn_workspace_bytes(dt, B, S, nl, dh, causal, bwd) for bwd in (False, True))
@@ -151,14 +148,14 @@ def test_attention_long_sequence_own_chunk_length(causal, monkeypatch):
 # "1", "3" = workspace and chunks of that many 64-row tile steps (every strip longer than that is cut).
 @pytest.mark.parametrize("dtype,chunk", [("bf16", None), ("bf16", "auto"), ("bf16", "1"), ("bf16", "3"), ("f32", None)])
 @pytest.mark.parametrize("causal", [True, False])
-def test_attention_fwd_bwd(dtype, chunk, causal, monkeypatch):
+def test_attention_fwd_bwd(dtype, chunk, causal, tune):
     import torch
     import paper_2111_05972_amd as pkg
     dt = pkg.TPL_BF16 if dtype == "bf16" else pkg.TPL_F32
     tol = 2e-2 if dtype == "bf16" else 1e-4
-    monkeypatch.delenv("TPL_ATTN_CHUNK", raising=False)
+    tune.set("attn_chunk", None)
     if chunk not in (None, "auto"):
-        monkeypatch.setenv("TPL_ATTN_CHUNK", chunk)
+        tune.set("attn_chunk", chunk)
     for ci, (B, S, nl, dh) in enumerate(ATTN_CASES):
         print(f"\n[attn] {dtype} causal={causal} chunk={chunk} B={B} S={S} nl={nl} dh={dh}", flush=True)
         ws_f = ws_b = None

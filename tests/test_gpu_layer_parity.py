@@ -72,10 +72,10 @@ def test_flag_on_variant_of_headline_shape_small_seq():
 
 
 @pytest.mark.parametrize("chunk", ["1", "2"])
-def test_attention_strips_cut_into_chunks(chunk, monkeypatch):
+def test_attention_strips_cut_into_chunks(chunk, tune):
     """The layer with its attention strips cut into chunks of 1 or 2 tile steps (partials in the workspace,
     combined by a second kernel), and the same twice over: bit-identical."""
-    monkeypatch.setenv("TPL_ATTN_CHUNK", chunk)
+    tune.set("attn_chunk", chunk)
     cfg = small_variant(C[2], name="bf16-dh128-causal-chunks", hidden=1024, heads=8, head_dim=128,
                         intermediate=2048, tp_degree=4, tp_rank=2, seq=333, micro_batch=2, causal=True,
                         row_epilogue=True)
@@ -105,8 +105,7 @@ def test_partials_of_all_ranks_sum_to_unsharded_layer_on_gpu():
     acc = {k: 0.0 for k in ("y_a", "y_m", "dx_a", "dx_m")}
     for r in range(cfg0.tp_degree):
         cfg = small_variant(cfg0, tp_rank=r, row_epilogue=(r == 0))
-        sh = oracle.shard_params(d, cfg.tp_degree, r)
-        got = gpu_outputs(cfg, d, sh)
+        got = gpu_outputs(cfg, d)            # sharded by the product's own rule
         for k in acc:
             acc[k] = acc[k] + got[k].astype(np.float64)
     ref = {"y_a": ya_f, "y_m": ym_f, "dx_a": gr_f["dx_a"], "dx_m": gr_f["dx_m"]}

@@ -196,13 +196,13 @@ def test_simulated_ranks_match_oracle(dtype, H, nh, I, T, S, Bz, causal):
     # the simulated ranks of the oracle are themselves the unsharded layer
     full_ref = mo.reference_layer_fwd(x, g, Bz, S, causal, eps)
     np.testing.assert_allclose(np.concatenate(y_ref, axis=1), full_ref, atol=1e-9)
-    # activations pass through a 16-bit reduce-scatter between the pieces: use twice the one-kernel bound
-    tol = 2 * TOL[dtype]
+    tol = TOL[dtype]                         # the benchmark spec's bound, end to end over all the pieces
     errs = {}
     errs["y2"] = max_rel_err(np.concatenate(y2, axis=1), full_ref)
     errs["dx"] = max_rel_err(np.concatenate(dx, axis=1), np.concatenate(dx_ref, axis=1))
     for r in range(T):
         for k, v in gr_ref[r].items():
             errs[f"r{r}.{k}"] = max_rel_err(grads[r][k], v)
+    print("[memopt-layer] max-normalised errors: " + " ".join(f"{k}={e:.1e}" for k, e in errs.items()), flush=True)
     bad = {k: e for k, e in errs.items() if not e <= tol}
     assert not bad, f"over tolerance {tol}: {bad}"

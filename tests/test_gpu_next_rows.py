@@ -7,7 +7,7 @@ import oracle
 import synthetic
 from synthetic.configs import small_variant
 
-from gpu_util import compare, gpu_outputs, oracle_outputs, shard_inputs
+from gpu_util import compare, gpu_outputs, oracle_outputs, product_shard, shard_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -96,7 +96,7 @@ def test_checkpoint_backward_reproduces_saved_backward(cfg):
     dt = pkg.TPL_F32 if cfg.dtype == "f32" else pkg.TPL_BF16
     layer = pkg.TpLayer(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt,
                         cfg.causal, cfg.row_epilogue, cfg.head_dim, cfg.intermediate)
-    p = {k: pkg.to_device(v, dt) for k, v in sh.items()}
+    p = {k: pkg.to_device(v, dt) for k, v in product_shard(cfg, d).items()}
     x = {k: pkg.to_device(d[k], dt) for k in ("x_a", "x_m", "dy_a", "dy_m")}
     grads = layer.empty_grads()
     dx_a, dx_m = layer.empty_outputs()
@@ -108,8 +108,7 @@ def test_checkpoint_backward_reproduces_saved_backward(cfg):
     for k, v in got.items():
         if k in base:
             assert np.array_equal(v.float().cpu().numpy(), base[k]), k
-    if cfg.cfg_id != 5 or True:
-        ref = oracle_outputs(cfg, d, sh)
-        full = dict(base)
-        full.update({k: v.float().cpu().numpy() for k, v in got.items() if k in base})
-        compare(cfg, full, ref)
+    ref = oracle_outputs(cfg, d, sh)
+    full = dict(base)
+    full.update({k: v.float().cpu().numpy() for k, v in got.items() if k in base})
+    compare(cfg, full, ref)

@@ -169,3 +169,128 @@ def test_simulated_ranks_backward_equals_finite_differences_of_unsharded_layer(c
         np.testing.assert_allclose(gr[r]["b_dn"], ref["bdn"][rows], **tol)
         for k in ("g1", "b1", "g2", "b2"):
             np.testing.assert_allclose(gr[r][k], ref[k][rows], **tol)
+
+
+# ---------------------------------------------------------------- pins of this module's own attention and
+# unsharded reference layer against things outside it: the scalar definition, a hand-computed two-key case, the
+# speed-optimised oracle's attention, and PyTorch's CPU operators with autograd.
+def _qkv_case(seed, B=2, S=5, nl=3, dh=4):
+    rng = np.random.default_rng(seed)
+    return rng.normal(0, 1.0, (B * S, 3 * nl * dh)), rng.normal(0, 1.0, (B * S, nl * dh)), (B, S, nl, dh)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_matches_scalar_definition(causal):
+    """O[b,i,h,:] = sum_j softmax_j(q_i . k_j / sqrt(dh)) v_j with j <= i when causal, by plain loops."""
+    import math
+    qkv, _, (B, S, nl, dh) = _qkv_case(20)
+    o, _ = mo._attention(qkv, B, S, nl, dh, causal)
+    t = qkv.reshape(B, S, 3, nl, dh)
+    for b in range(B):
+        for h in range(nl):
+            for i in range(S):
+                js = range(i + 1) if causal else range(S)
+                logit = [sum(t[b, i, 0, h, c] * t[b, j, 1, h, c] for c in range(dh)) / math.sqrt(dh) for j in js]
+                mx = max(logit)
+                w = [math.exp(v - mx) for v in logit]
+                den = sum(w)
+                for c in range(dh):
+                    ref = sum(w[n] / den * t[b, j, 2, h, c] for n, j in enumerate(js))
+                    assert abs(o[b * S + i, h * dh + c] - ref) < 1e-12
+
+
+def test_attention_two_key_case_fixes_the_scale():
+    """One head of size 4, two keys with q.k = 2 ln 3 and 0: the weights are (0.75, 0.25) only with 1/sqrt(dh)."""
+    dh, S = 4, 2
+    q = np.zeros((S, dh)); k = np.zeros((S, dh)); v = np.zeros((S, dh))
+    q[:, 0] = 1.0
+    k[0, 0] = 2.0 * np.log(3.0)                      # logits (ln 3, 0) after the division by sqrt(4) = 2
+    v[0, 0], v[1, 0] = 1.0, 5.0
+    qkv = np.concatenate([q, k, v], axis=1)
+    o, (_, _, _, P) = mo._attention(qkv, 1, S, 1, dh, False)
+    np.testing.assert_allclose(P[0, 0], [[0.75, 0.25], [0.75, 0.25]], atol=1e-14)
+    np.testing.assert_allclose(o[:, 0], [2.0, 2.0], atol=1e-14)
+    oc, (_, _, _, Pc) = mo._attention(qkv, 1, S, 1, dh, True)
+    np.testing.assert_allclose(Pc[0, 0], [[1.0, 0.0], [0.75, 0.25]], atol=1e-14)     # key 1 hidden from query 0
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_and_its_backward_match_pytorch_and_the_other_oracle(causal):
+    import torch
+    import torch.nn.functional as F
+    from oracle import tp_layer_oracle as so
+    qkv, d_o, (B, S, nl, dh) = _qkv_case(21)
+    o, saved = mo._attention(qkv, B, S, nl, dh, causal)
+    dqkv = mo._attention_bwd(d_o, saved, B, S, nl, dh)
+    tq = torch.tensor(qkv, dtype=torch.float64, requires_grad=True)
+    t = tq.reshape(B, S, 3, nl, dh).permute(2, 0, 3, 1, 4)
+    to = F.scaled_dot_product_attention(t[0], t[1], t[2], is_causal=causal).permute(0, 2, 1, 3).reshape(B * S, nl * dh)
+    (to * torch.tensor(d_o)).sum().backward()
+    np.testing.assert_allclose(o, to.detach().numpy(), atol=1e-12)
+    np.testing.assert_allclose(dqkv, tq.grad.numpy(), atol=1e-12)
+    Q, K, V = so._split_heads(qkv, B, S, nl, dh)
+    O2, P2, _ = so.attention_fwd(Q, K, V, causal)
+    np.testing.assert_allclose(o, O2.transpose(0, 2, 1, 3).reshape(B * S, nl * dh), atol=1e-13)
+    np.testing.assert_allclose(saved[3], P2, atol=1e-14)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_reference_layer_matches_pytorch_pre_normalised_blocks(causal):
+    """y1 = x + Attn(LN1(x)), y2 = y1 + MLP(LN2(y1)) written with PyTorch's CPU operators."""
+    import torch
+    import torch.nn.functional as F
+    g, x, _ = _tiny(5, H=24, nh=4, I=40, B=2, S=6)
+    B, S, eps = 2, 6, 1e-5
+    H, nh = x.shape[1], g["nh"]
+    dh = H // nh
+    T_ = lambda a: torch.tensor(np.asarray(a), dtype=torch.float64)   # noqa: E731
+    tx = T_(x)
+    h1 = F.layer_norm(tx, (H,), T_(g["g1"]), T_(g["b1"]), eps)
+    qkv = F.linear(h1, T_(g["Wqkv"]).T, T_(g["bqkv"])).reshape(B, S, 3, nh, dh).permute(2, 0, 3, 1, 4)
+    o = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2], is_causal=causal).permute(0, 2, 1, 3).reshape(B * S, H)
+    y1 = tx + F.linear(o, T_(g["Wo"]).T, T_(g["bo"]))
+    h2 = F.layer_norm(y1, (H,), T_(g["g2"]), T_(g["b2"]), eps)
+    y2 = y1 + F.linear(F.gelu(F.linear(h2, T_(g["Wup"]).T, T_(g["bup"]))), T_(g["Wdn"]).T, T_(g["bdn"]))
+    np.testing.assert_allclose(mo.reference_layer_fwd(x, g, B, S, causal, eps), y2.numpy(), atol=1e-11)
+
+
+@pytest.mark.parametrize("mutation", ["no_softmax_scale", "mask_excludes_diagonal", "dk_uses_k", "post_norm_layer"])
+def test_memopt_pins_fail_on_planted_mistakes(monkeypatch, mutation):
+    """Each mistake is planted in this oracle (CPU only); at least one of the pins above must fail."""
+    if mutation == "no_softmax_scale":
+        orig = mo._attention
+        monkeypatch.setattr(mo, "_attention", lambda q, B, S, nl, dh, c: orig(
+            np.concatenate([q[:, :nl * dh] * np.sqrt(dh), q[:, nl * dh:]], axis=1), B, S, nl, dh, c))
+        victims = [lambda: test_attention_matches_scalar_definition(True), test_attention_two_key_case_fixes_the_scale,
+                   lambda: test_attention_and_its_backward_match_pytorch_and_the_other_oracle(False),
+                   lambda: test_reference_layer_matches_pytorch_pre_normalised_blocks(True)]
+    elif mutation == "mask_excludes_diagonal":
+        real_tril = np.tril
+        monkeypatch.setattr(mo.np, "tril", lambda a, k=0: real_tril(a, k - 1) | (real_tril(a, 0) & ~real_tril(a, -1) & (np.arange(a.shape[0]) == 0)[:, None]))
+        victims = [lambda: test_attention_matches_scalar_definition(True), test_attention_two_key_case_fixes_the_scale]
+    elif mutation == "dk_uses_k":
+        orig = mo._attention_bwd
+
+        def bad(dO, saved, B, S, nl, dh):
+            Q, K, V, P = saved
+            good = orig(dO, saved, B, S, nl, dh).reshape(B * S, 3, nl * dh)
+            wrong = orig(dO, (K, K, V, P), B, S, nl, dh).reshape(B * S, 3, nl * dh)
+            good[:, 1] = wrong[:, 1]
+            return good.reshape(B * S, 3 * nl * dh)
+        monkeypatch.setattr(mo, "_attention_bwd", bad)
+        victims = [lambda: test_attention_and_its_backward_match_pytorch_and_the_other_oracle(True),
+                   lambda: test_simulated_ranks_backward_equals_finite_differences_of_unsharded_layer(False)]
+    else:
+        orig = mo.reference_layer_fwd
+
+        def post_norm(x, g, B, S, causal, eps):          # normalises after the residual sum instead of before the block
+            gg = dict(g)
+            H = np.asarray(x).shape[1]
+            gg["g1"], gg["b1"] = np.ones(H), np.zeros(H)
+            return orig(x, gg, B, S, causal, eps)
+        monkeypatch.setattr(mo, "reference_layer_fwd", post_norm)
+        victims = [lambda: test_reference_layer_matches_pytorch_pre_normalised_blocks(False),
+                   lambda: test_simulated_ranks_equal_unsharded_layer(2, True)]
+    for v in victims:
+        with pytest.raises(AssertionError):
+            v()
