@@ -232,6 +232,17 @@ size_t tp_layer_slice_epilogue_workspace_bytes(int64_t M, int64_t N);
 int tp_layer_slice_epilogue_bwd(int dtype, int act, int64_t M, int64_t N, const void* dout, const void* u,
                                 void* din, void* dbias, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* tp_layer_slice_epilogue_bwd for callers that cannot allocate or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the column-sum partials in a
+ * static device array of the library instead of `ws`.  The array is tp_layer_static_scratch_bytes() (4 MiB) per
+ * GPU and is held until the process ends; a problem whose partials do not fit
+ * (tp_layer_slice_epilogue_workspace_bytes(M, N) above that size, i.e. ceil(M / 64) * N floats) is refused with
+ * TPL_EWORKSPACE.  The call allocates nothing and never synchronises.  All calls on one GPU share the array:
+ * calls that overlap on one GPU (different streams without ordering) race on it; stream-ordered calls do not. */
+size_t tp_layer_static_scratch_bytes(void);
+int tp_layer_slice_epilogue_bwd_static(int dtype, int act, int64_t M, int64_t N, const void* dout, const void* u,
+                                       void* din, void* dbias, void* hip_stream);
+
 /* One GEMM of the path with its fused epilogue, exposed for per-kernel tests and timing:
  *   C[M,N] = epi( opA(A) opB(B) ),  element type `dtype`, float accumulation.
  * trans_a == 0: A is [M,K] row-major, else A is [K,M] row-major (used as its transpose).

@@ -16,7 +16,7 @@ from .binding import (  # noqa: F401
     tp_layer_ln_moments, tp_layer_ln_stats, tp_layer_ln_apply_fwd, tp_layer_ln_apply_bwd_sums,
     tp_layer_ln_apply_workspace_bytes, tp_layer_ln_apply_bwd,
     tp_layer_slice_epilogue_fwd, tp_layer_slice_epilogue_workspace_bytes, tp_layer_slice_epilogue_bwd,
-    TPL_ACT_NONE, TPL_ACT_GELU,
+    TPL_ACT_NONE, TPL_ACT_GELU, tp_layer_static_scratch_bytes, tp_layer_slice_epilogue_bwd_static,
 )
 
 

@@ -88,6 +88,8 @@ def load_library():
         "tp_layer_slice_epilogue_fwd": (ci, [ci, ci, i64, i64, _vp, _vp, _vp, _vp, _vp, _vp]),
         "tp_layer_slice_epilogue_workspace_bytes": (sz, [i64, i64]),
         "tp_layer_slice_epilogue_bwd": (ci, [ci, ci, i64, i64, _vp, _vp, _vp, _vp, _vp, sz, _vp]),
+        "tp_layer_static_scratch_bytes": (sz, []),
+        "tp_layer_slice_epilogue_bwd_static": (ci, [ci, ci, i64, i64, _vp, _vp, _vp, _vp, _vp]),
         "tp_layer_set_option": (ci, [ctypes.c_char_p, ctypes.c_char_p]),
         "tp_layer_profile": (ci, [ci]),
         "tp_layer_profile_read": (ci, [ctypes.POINTER(ctypes.c_float), ci, ctypes.POINTER(ci)]),
@@ -280,6 +282,16 @@ def tp_layer_slice_epilogue_bwd(dtype, act, M, N, dout, u, din, dbias, ws, ws_by
                                                     _ptr(ws), (_nbytes(ws) or 0) if ws_bytes is None else ws_bytes,
                                                     _stream(stream))
     return _checked(rc, "tp_layer_slice_epilogue_bwd", check)
+
+
+def tp_layer_static_scratch_bytes():
+    return load_library().tp_layer_static_scratch_bytes()
+
+
+def tp_layer_slice_epilogue_bwd_static(dtype, act, M, N, dout, u, din, dbias, stream=None, check=True):
+    rc = load_library().tp_layer_slice_epilogue_bwd_static(dtype, act, M, N, _ptr(dout), _ptr(u), _ptr(din),
+                                                           _ptr(dbias), _stream(stream))
+    return _checked(rc, "tp_layer_slice_epilogue_bwd_static", check)
 
 
 def tp_layer_set_option(name, value=None, check=True):

@@ -67,6 +67,10 @@ hipError_t attn_simple_bwd(const AttnArgs& a);
 // out[n] = sum_m X[m,n]  (bias gradients), deterministic.
 hipError_t colsum(int dtype, int64_t M, int64_t N, const void* X, void* out, float* scratch, hipStream_t s);
 size_t colsum_scratch_bytes(int64_t M, int64_t N);
+// The library's own scratch (a static device array, one copy per GPU) for entry points that may not allocate:
+// *ptr = its address on the current device.  Calls that use it on one GPU share it.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)4 << 20;
+hipError_t static_scratch(void** ptr);
 // out[n] = sum over slabs of part[slab * stride + n], in slab order.
 hipError_t sum_partials_strided(int dtype, int64_t slabs, int64_t N, const float* part, int64_t stride,
                                 void* out, hipStream_t s);

@@ -2,6 +2,8 @@
 // They are the only path for float tensors and cover bfloat16 shapes the MFMA kernels do not take.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "device_math.h"
 #include "kernels.h"
 
@@ -406,6 +408,31 @@ hipError_t sum_partials_strided(int dtype, int64_t slabs, int64_t N, const float
     if (dtype == F32) hipLaunchKernelGGL(colsum_stage2<float>, g2, dim3(256), 0, s, slabs, N, stride, part, (float*)out);
     else hipLaunchKernelGGL(colsum_stage2<bf16_t>, g2, dim3(256), 0, s, slabs, N, stride, part, (bf16_t*)out);
     return hipGetLastError();
+}
+
+// Scratch for the entry points that may not allocate: one array per GPU, held until the process ends.  In host
+// code the array's name is only a handle; its device address is looked up once per device (with that device
+// current) and that pointer is what every launch and copy uses.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+hipError_t static_scratch(void** ptr) {
+    constexpr int MAX_DEV = 64;
+    static void* per_device[MAX_DEV] = {};
+    static std::mutex mu;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEV) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    return hipSuccess;
 }
 
 hipError_t colsum(int dtype, int64_t M, int64_t N, const void* X, void* out, float* scratch,

@@ -620,6 +620,30 @@ int tp_layer_slice_epilogue_bwd(int dtype, int act, int64_t M, int64_t N, const 
     return hip_rc(colsum(dtype, M, N, d, dbias, (float*)ws, s));
 }
 
+size_t tp_layer_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+int tp_layer_slice_epilogue_bwd_static(int dtype, int act, int64_t M, int64_t N, const void* dout, const void* u,
+                                       void* din, void* dbias, void* hip_stream) {
+    int rc = ew_check(dtype, M, N);
+    if (rc) return rc;
+    if (act != TPL_ACT_NONE && act != TPL_ACT_GELU) return TPL_EINVAL;
+    if (!dout || !dbias || (act == TPL_ACT_GELU && (!u || !din))) return TPL_EINVAL;
+    const void* ptrs[] = {dout, u, din, dbias};
+    for (const void* q : ptrs) if (misaligned(q)) return TPL_EALIGN;
+    // the column-sum partials must fit the static array: nothing is allocated here
+    if (colsum_scratch_bytes(M, N) > STATIC_SCRATCH_BYTES) return TPL_EWORKSPACE;
+    void* ws = nullptr;
+    if (static_scratch(&ws) != hipSuccess) return TPL_EHIP;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const void* d = dout;
+    if (act == TPL_ACT_GELU) {
+        if (gelu_bwd(dtype, M, N, dout, u, din, s) != hipSuccess) return TPL_EHIP;
+        d = din;
+    }
+    // every partial the second stage reads is written by the first in the same call: nothing to clear
+    return hip_rc(colsum(dtype, M, N, d, dbias, (float*)ws, s));
+}
+
 size_t tp_layer_gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
     return std::max(gemm_ws(dtype, M, N, K), ALIGN);
@@ -717,7 +741,7 @@ const char* tp_layer_strerror(int status) {
         case TPL_OK: return "ok";
         case TPL_EINVAL: return "invalid argument (null pointer, non-positive or non-dividing size)";
         case TPL_EUNSUPPORTED: return "valid layer but unsupported shape or dtype";
-        case TPL_EWORKSPACE: return "workspace too small";
+        case TPL_EWORKSPACE: return "workspace too small (for a *_static entry point: the problem needs more scratch than the library's static array holds)";
         case TPL_EALIGN: return "pointer not 16-byte aligned";
         case TPL_EHIP: return "HIP launch failed";
         default: return "unknown status";
