@@ -233,9 +233,9 @@ def main():
                     help="layer: tp_layer_fwd + tp_layer_bwd (the headline metric); layer-checkpoint: tp_layer_fwd + "
                          "tp_layer_bwd_recompute; ln: replicated LayerNorm forward + backward on the config's [M, H]; "
                          "memopt: one rank's local compute in the memory-optimised distribution at the config's widths")
-    ap.add_argument("--side-stream", action="store_true",
-                    help="time the two-chain schedule (TPL_SIDE_STREAM: the MLP block of a pass on a second, "
-                         "library-owned stream) instead of the default, everything on the caller's stream")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="time the plain schedule, every kernel on the caller's stream, instead of the two-chain "
+                         "schedule (TPL_SIDE_STREAM: the MLP block of a pass on a second, library-owned stream)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -273,7 +273,7 @@ def main():
     host_sh = pkg.shard_params(d, cfg.tp_degree if cfg.global_params else 1,
                                cfg.tp_rank if cfg.global_params else 0)
     layer = pkg.TpLayer(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt,
-                        cfg.causal, cfg.row_epilogue, cfg.head_dim, cfg.intermediate, side_stream=args.side_stream)
+                        cfg.causal, cfg.row_epilogue, cfg.head_dim, cfg.intermediate, side_stream=not args.single_stream)
     p = {k: pkg.to_device(v, dt) for k, v in host_sh.items()}
     x = {k: pkg.to_device(d[k], dt) for k in ("x_a", "x_m", "dy_a", "dy_m")}
     y_a, y_m = layer.empty_outputs()

@@ -146,6 +146,10 @@ constexpr unsigned OOB_HALF = 0x80000000u;     // out of bounds for operands bel
 __device__ __forceinline__ int xor16(int k) { return (((k >> 1) & 1) << 1) | (((k >> 3) & 1) << 2); }
 // K16: K-major chunk positions for tiles read as 16-row fragments (swz_k32_16 below).
 __device__ __forceinline__ int swz_k32_16(int row) { return (row >> 1) & 3; }
+// k row (0..31) of the MN-major stage tile of R = 64 T columns that load j of wavefront `wave` fetches for this lane.
+template <int T> __device__ __forceinline__ int mn_krow(int wave, int j, int lane) {
+    return ((wave * T + j) * 64 + lane) / (64 * T / 8);
+}
 template <bool KMAJ, int T, bool XOR16 = false, bool K16 = false>
 __device__ __forceinline__ void dma_offsets(unsigned (&off)[T], bool (&mn_ok)[T], int& kcol, int ld,
                                             int mn0, int MN, int wave, int lane) {
@@ -157,8 +161,8 @@ __device__ __forceinline__ void dma_offsets(unsigned (&off)[T], bool (&mn_ok)[T]
             int row = block * 16 + (lane >> 2);
             int c = (lane & 3) ^ (K16 ? swz_k32_16(row) : swz_k32(row));
             kcol = c * 8;                                   // same for every j
-            mn_ok[j] = true;                                // rows beyond MN fall outside the buffer
-            off[j] = (unsigned)(((int64_t)(mn0 + row) * ld + c * 8) * 2);
+            mn_ok[j] = true;                                // rows beyond MN point past the buffer
+            off[j] = mn0 + row < MN ? (unsigned)(((int64_t)(mn0 + row) * ld + c * 8) * 2) : OOB_HALF;
         } else {
             int idx = block * 64 + lane;                    // physical chunk index inside the stage tile
             int k = idx / (R / 8);
@@ -751,6 +755,37 @@ struct SpecTile {
     }
 };
 
+// One operand's loads of one k range [k0, k0 + KSPAN) by a fetching wavefront: NL loads, load i to LDS block
+// lds_first + 1024 i.  off[i] is the lane's loop-invariant byte offset (k = 0; rows or columns outside the matrix
+// already point past the buffer), kin[i] the lane's k position inside the range (K-major: its chunk's first k;
+// MN-major: its row), kstep_bytes the bytes per unit of k (2 for K-major, 2 ld for MN-major).
+//  * range inside the K share: the k position is the load's SCALAR offset, the lane offset is used as it is;
+//  * range past the end of the share: a descriptor of zero records (nothing is read, zeros land in LDS);
+//  * range that straddles the end (K not a multiple of the range): per-lane check, the only case with vector
+//    instructions.  A vector instruction issued by a fetching wavefront takes an issue slot from the matrix
+//    instructions of the math wavefront on the same SIMD (measured: about 2 cycles of matrix-pipe time each), which
+//    is why the steady state has none.
+template <int NL, int KSPAN>
+__device__ __forceinline__ void fetch_range(const i32x4& rsrc, unsigned lds_first, const unsigned (&off)[NL],
+                                            const int (&kin)[NL], int k0, int kend, unsigned kstep_bytes) {
+    if (k0 >= kend) {
+        i32x4 r = rsrc;
+        r[2] = 0;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) buffer_load_lds_b128_s(r, lds_first + i * 1024, off[i], 0u);
+    } else if (k0 + KSPAN <= kend) {
+        // (the compiler does not always see that the product is wave-uniform)
+        const unsigned so = (unsigned)__builtin_amdgcn_readfirstlane((int)((unsigned)k0 * kstep_bytes));
+#pragma unroll
+        for (int i = 0; i < NL; ++i) buffer_load_lds_b128_s(rsrc, lds_first + i * 1024, off[i], so);
+    } else {
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            buffer_load_lds_b128(rsrc, lds_first + i * 1024,
+                                 k0 + kin[i] < kend ? off[i] + (unsigned)k0 * kstep_bytes : OOB_OFFSET);
+    }
+}
+
 // K-major tile with rows of 128 bytes (64 k): 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7),
 // so the 16 rows a quarter-wavefront reads at one k are spread over all banks.
 __device__ __forceinline__ int swz_k64(int row) { return (row >> 1) & 7; }
@@ -779,54 +814,55 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec_kernel(GemmParams p) {
         const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)(A_KMAJ ? p.M : p.K) * p.lda * 2));
         const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
         const unsigned lds_a = (unsigned)(uintptr_t)(lds_void_ptr)smem, lds_b = lds_a + A_BYTES;
-        // B and narrow A: as in the kernel above
-        unsigned offb[TN], offa[TM];
-        bool okb[TN], oka[TM];
-        int kcb, kca = 0;
-        dma_offsets<B_KMAJ, TN>(offb, okb, kcb, p.ldb, n0, p.N, w, lane);
-        // wide A: load q (0 .. 2 TM - 1) of a unit covers rows 8 (2 TM w + q) .. + 7, lane l the chunk at
-        // LDS position l % 8 of row l / 8
-        unsigned offw[2 * TM];
-        int kcw[2 * TM];
+        // Lane offsets of this wavefront's loads (see fetch_range): B and a narrow A as in the kernel above; a wide A
+        // unit is 2 TM loads, load q covering rows 8 (2 TM w + q) .. + 7, lane l the chunk at LDS position l % 8 of
+        // row l / 8.
+        unsigned offb[TN], offa[TM], offw0[TM], offw1[TM];
+        int kinb[TN], kina[TM], kinw0[TM], kinw1[TM];
+        {
+            bool okb[TN];
+            int kc;
+            dma_offsets<B_KMAJ, TN>(offb, okb, kc, p.ldb, n0, p.N, w, lane);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (!B_KMAJ) offb[j] = okb[j] ? offb[j] : OOB_HALF;
+                kinb[j] = B_KMAJ ? kc : mn_krow<TN>(w, j, lane);
+            }
+        }
         if (WIDE) {
 #pragma unroll
             for (int q = 0; q < 2 * TM; ++q) {
-                int row = (w * 2 * TM + q) * 8 + (lane >> 3);
-                int c = (lane & 7) ^ swz_k64(row);
-                kcw[q] = c * 8;
-                offw[q] = (unsigned)(((int64_t)(m0 + row) * p.lda + c * 8) * 2);
+                const int row = (w * 2 * TM + q) * 8 + (lane >> 3);
+                const int c = (lane & 7) ^ swz_k64(row);
+                const unsigned o = m0 + row < p.M ? (unsigned)(((int64_t)(m0 + row) * p.lda + c * 8) * 2) : OOB_HALF;
+                if (q < TM) { offw0[q] = o; kinw0[q] = c * 8; }
+                else { offw1[q - TM] = o; kinw1[q - TM] = c * 8; }
             }
         } else {
-            dma_offsets<A_KMAJ, TM>(offa, oka, kca, p.lda, m0, p.M, w, lane);
-        }
-        // k-steps kt and wide units u below count from the start of this workgroup's K share
-        auto load_b = [&](int kt) {                               // k-step kt of B into its slot
-            const unsigned buf = lds_b + (kt % NB) * ST::B_SLOT;
-            const int k0 = (sh.kt0 + kt) * DK;
-            const unsigned step = B_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.ldb * 2);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                bool ok = B_KMAJ ? (k0 + kcb < sh.kend) : (okb[j] && k0 < sh.kend);
-                buffer_load_lds_b128(rb, buf + (w * TN + j) * 1024, ok ? offb[j] + step : OOB_OFFSET);
-            }
-        };
-        auto load_a32 = [&](int kt) {
-            const unsigned buf = lds_a + (kt % NB) * ST::A_SLOT32;
-            const int k0 = (sh.kt0 + kt) * DK;
-            const unsigned step = A_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.lda * 2);
+            bool oka[TM];
+            int kc;
+            dma_offsets<A_KMAJ, TM>(offa, oka, kc, p.lda, m0, p.M, w, lane);
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
-                bool ok = A_KMAJ ? (k0 + kca < sh.kend) : (oka[j] && k0 < sh.kend);
-                buffer_load_lds_b128(ra, buf + (w * TM + j) * 1024, ok ? offa[j] + step : OOB_OFFSET);
+                if (!A_KMAJ) offa[j] = oka[j] ? offa[j] : OOB_HALF;
+                kina[j] = A_KMAJ ? kc : mn_krow<TM>(w, j, lane);
             }
+        }
+        const unsigned kb_bytes = B_KMAJ ? 2u : (unsigned)p.ldb * 2u, ka_bytes = A_KMAJ ? 2u : (unsigned)p.lda * 2u;
+        // k-steps kt and wide units u below count from the start of this workgroup's K share
+        auto load_b = [&](int kt) {                               // k-step kt of B into its slot
+            fetch_range<TN, DK>(rb, lds_b + (kt % NB) * ST::B_SLOT + w * TN * 1024, offb, kinb, (sh.kt0 + kt) * DK, sh.kend,
+                                kb_bytes);
+        };
+        auto load_a32 = [&](int kt) {
+            fetch_range<TM, DK>(ra, lds_a + (kt % NB) * ST::A_SLOT32 + w * TM * 1024, offa, kina, (sh.kt0 + kt) * DK, sh.kend,
+                                ka_bytes);
         };
         auto load_a64 = [&](int u, int half) {                    // half 0/1 of unit u (k = 64 u ..)
-            const unsigned buf = lds_a + (u % NAW) * ST::A_SLOT64;
-            const int ua = (sh.kt0 >> 1) + u;
-#pragma unroll
-            for (int q = half * TM; q < (half + 1) * TM; ++q)
-                buffer_load_lds_b128(ra, buf + (w * 2 * TM + q) * 1024,
-                                     64 * ua + kcw[q] < sh.kend ? offw[q] + (unsigned)ua * 128u : OOB_OFFSET);
+            const unsigned buf = lds_a + (u % NAW) * ST::A_SLOT64 + (w * 2 * TM + half * TM) * 1024;
+            const int k0 = 64 * ((sh.kt0 >> 1) + u);
+            if (half == 0) fetch_range<TM, 64>(ra, buf, offw0, kinw0, k0, sh.kend, 2u);
+            else fetch_range<TM, 64>(ra, buf, offw1, kinw1, k0, sh.kend, 2u);
         };
         // prologue: everything the rings hold, except the second half of the last wide unit
         if (WIDE) {
@@ -1011,36 +1047,34 @@ __global__ __launch_bounds__(512) void gemm_bf16_spec16_kernel(GemmParams p) {
         const i32x4 ra = make_rsrc(p.A, (unsigned)((int64_t)p.M * p.lda * 2));
         const i32x4 rb = make_rsrc(p.B, (unsigned)((int64_t)(B_KMAJ ? p.N : p.K) * p.ldb * 2));
         const unsigned lds_a = (unsigned)(uintptr_t)(lds_void_ptr)smem, lds_b = lds_a + A_BYTES;
-        unsigned offb[TN];
-        bool okb[TN];
-        int kcb;
-        dma_offsets<B_KMAJ, TN, true, true>(offb, okb, kcb, p.ldb, n0, p.N, w, lane);
-        unsigned offw[LA];
-        int kcw[LA];
-#pragma unroll
-        for (int q = 0; q < LA; ++q) {
-            int row = (w * LA + q) * 8 + (lane >> 3);
-            int c = (lane & 7) ^ swz_k64(row);
-            kcw[q] = c * 8;
-            offw[q] = (unsigned)(((int64_t)(m0 + row) * p.lda + c * 8) * 2);
-        }
-        auto load_b = [&](int kt) {                               // k-step kt (of this K share) of B into its slot
-            const unsigned buf = lds_b + (kt % NB) * ST::B_SLOT;
-            const int k0 = (sh.kt0 + kt) * DK;
-            const unsigned step = B_KMAJ ? (unsigned)k0 * 2u : (unsigned)((int64_t)k0 * p.ldb * 2);
+        // lane offsets of this wavefront's loads (see fetch_range)
+        unsigned offb[TN], offw[LA];
+        int kinb[TN], kinw[LA];
+        {
+            bool okb[TN];
+            int kc;
+            dma_offsets<B_KMAJ, TN, true, true>(offb, okb, kc, p.ldb, n0, p.N, w, lane);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                bool ok = B_KMAJ ? (k0 + kcb < sh.kend) : (okb[j] && k0 < sh.kend);
-                buffer_load_lds_b128(rb, buf + (w * TN + j) * 1024, ok ? offb[j] + step : OOB_OFFSET);
+                if (!B_KMAJ) offb[j] = okb[j] ? offb[j] : OOB_HALF;
+                kinb[j] = B_KMAJ ? kc : mn_krow<TN>(w, j, lane);
             }
+        }
+#pragma unroll
+        for (int q = 0; q < LA; ++q) {
+            const int row = (w * LA + q) * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ swz_k64(row);
+            kinw[q] = c * 8;
+            offw[q] = m0 + row < p.M ? (unsigned)(((int64_t)(m0 + row) * p.lda + c * 8) * 2) : OOB_HALF;
+        }
+        const unsigned kb_bytes = B_KMAJ ? 2u : (unsigned)p.ldb * 2u;
+        auto load_b = [&](int kt) {                               // k-step kt (of this K share) of B into its slot
+            fetch_range<TN, DK>(rb, lds_b + (kt % NB) * ST::B_SLOT + w * TN * 1024, offb, kinb, (sh.kt0 + kt) * DK, sh.kend,
+                                kb_bytes);
         };
         auto load_a = [&](int u) {                                // unit u (k-steps 2u, 2u+1 of this K share) of A
-            const unsigned buf = lds_a + (u % NAW) * ST::A_SLOT64;
-            const int ua = (sh.kt0 >> 1) + u;
-#pragma unroll
-            for (int q = 0; q < LA; ++q)
-                buffer_load_lds_b128(ra, buf + (w * LA + q) * 1024,
-                                     64 * ua + kcw[q] < sh.kend ? offw[q] + (unsigned)ua * 128u : OOB_OFFSET);
+            fetch_range<LA, 64>(ra, lds_a + (u % NAW) * ST::A_SLOT64 + w * LA * 1024, offw, kinw, 64 * ((sh.kt0 >> 1) + u),
+                                sh.kend, 2u);
         };
         load_a(0); load_b(0); load_b(1); load_a(1); load_b(2); load_b(3);
         wait_vmcnt<LA + 3 * LBW>();                               // unit 0 and B k-step 0 have landed
@@ -1337,6 +1371,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_x16s_kernel(GemmParams p) {
     __builtin_amdgcn_s_barrier();
     epilogue16<TL>(p, acc, smem, wave, lane, m0, n0, sh.partial);
 }
+
+
 
 bool gemm_bf16_supported(const GemmArgs& a) {
     if (a.dtype != BF16) return false;

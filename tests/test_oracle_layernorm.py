@@ -84,3 +84,45 @@ def test_planted_mistake_unbiased_variance_is_caught(monkeypatch):
     monkeypatch.setattr(oracle, "layernorm_fwd", bad)
     with pytest.raises(AssertionError):
         test_matches_pytorch_layer_norm_and_autograd()
+
+
+# ---------------------------------------------------------------- the LayerNorm + shard composition used by the GPU test
+@pytest.mark.parametrize("pre_ln", [False, True])
+def test_composed_layer_backward_matches_finite_differences(pre_ln):
+    """tests/test_gpu_ln_compose.py chains LayerNorm and the shard's two blocks by hand (two shard calls per pass);
+    here the same chain, run on the oracle, is checked against central differences of its own forward."""
+    import synthetic
+    from synthetic.configs import small_variant
+    from test_gpu_ln_compose import OracleBackend, compose
+    cfg = small_variant(synthetic.CONFIGS[1], name="ln-compose-tiny", hidden=16, heads=2, head_dim=8, intermediate=32,
+                        tp_degree=2, tp_rank=0, seq=4, micro_batch=2, causal=True, sigma_w=0.3, sigma_x=1.0)
+    g = {k: v.astype(np.float64) for k, v in synthetic.make_inputs(cfg).items()}
+    rng = np.random.default_rng(5)
+    H = cfg.hidden
+    ln = {f"{n}{i}": rng.normal(1.0 if n == "g" else 0.0, 0.3, H) for n in "gb" for i in (1, 2, 3)}
+    h, dout = g["x_a"], g["dy_a"]
+
+    def loss(h_=h, ln_=ln, g_=g):
+        return float((compose(OracleBackend(cfg, g_), cfg, pre_ln, h_, dout, ln_)["out"] * dout).sum())
+
+    res = compose(OracleBackend(cfg, g), cfg, pre_ln, h, dout, ln)
+    eps = 1e-6
+
+    def fd(arr, setter):
+        out = np.zeros_like(arr)
+        for idx in np.ndindex(arr.shape):
+            p, m = arr.copy(), arr.copy()
+            p[idx] += eps
+            m[idx] -= eps
+            out[idx] = (setter(p) - setter(m)) / (2 * eps)
+        return out
+
+    np.testing.assert_allclose(res["dh"], fd(h, lambda v: loss(h_=v)), rtol=2e-5, atol=1e-7)
+    for k in ("g1", "b1", "g2", "b2"):
+        np.testing.assert_allclose(res["d" + k], fd(ln[k], lambda v: loss(ln_={**ln, k: v})), rtol=2e-5, atol=1e-7)
+    # a weight gradient of each block, rank 1's shard: rows / columns r of the unsharded matrices
+    nl, dh, Il = cfg.local_heads, cfg.head_dim, cfg.local_mlp
+    gWo = fd(g["Wo"], lambda v: loss(g_={**g, "Wo": v}))
+    np.testing.assert_allclose(res["r1.dw_o"], gWo[nl * dh:2 * nl * dh], rtol=2e-5, atol=1e-7)
+    gWup = fd(g["Wup"], lambda v: loss(g_={**g, "Wup": v}))
+    np.testing.assert_allclose(res["r1.dw_up"], gWup[:, Il:2 * Il], rtol=2e-5, atol=1e-7)
