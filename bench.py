@@ -82,7 +82,7 @@ def bench_layernorm(args, cfg, dt, pkg, torch, synthetic):
     err = max(oracle.max_rel_err(y.float().cpu().numpy(), yr), oracle.max_rel_err(dz.float().cpu().numpy(), dzr),
               oracle.max_rel_err(dg.float().cpu().numpy(), dgr), oracle.max_rel_err(db.float().cpu().numpy(), dbr))
     gbs = (fwd_bytes + bwd_bytes) / (ms * 1e-3) / 1e9
-    print(json.dumps({
+    return ({
         "metric": "GB/s of algorithmic HBM bytes, replicated LayerNorm fwd+bwd", "value": round(gbs, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
@@ -93,7 +93,7 @@ def bench_layernorm(args, cfg, dt, pkg, torch, synthetic):
                      "bwd": {"ms": round(bwd_ms, 4), "GBps": round(bwd_bytes / bwd_ms / 1e6, 1)}},
         "cpu_baseline": {"value": round((fwd_bytes + bwd_bytes) / cpu_s / 1e9, 2), "unit": "GB/s", "cores": os.cpu_count(),
                          "kind": "oracle", "sample": "full workload, one fwd+bwd pass", "seconds": round(cpu_s, 2)},
-        "max_rel_err_vs_oracle": err}))
+        "max_rel_err_vs_oracle": err})
 
 
 def bench_memopt(args, cfg, dt, pkg, torch, synthetic):
@@ -207,7 +207,7 @@ def bench_memopt(args, cfg, dt, pkg, torch, synthetic):
                "w_up": (rank.grads["w_up"], dw_up), "w_qkv": (rank.grads["w_qkv"], dw_qkv), "b_up": (rank.grads["b_up"], db_up),
                "g2": (rank.grads["g2"], dg2), "g1": (rank.grads["g1"], dg1), "part_dn": (rank._part(H), part_dn)}
         err = max(max_rel_err(N(a), b) for a, b in got.values())
-    print(json.dumps({
+    return ({
         "metric": "TFLOP/s (fwd+bwd), one rank's local compute, memory-optimised distribution; % bf16 MFMA peak",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -216,64 +216,39 @@ def bench_memopt(args, cfg, dt, pkg, torch, synthetic):
                    "hidden": H, "heads": nh, "tp_degree": T, "seq": S, "micro_batch": Bz, "causal": cfg.causal,
                    "model_tflop_per_step": round((f_fwd + f_bwd) / 1e12, 4),
                    "collectives": "stood in for by fixed seeded tensors; not timed"},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "max_rel_err_vs_oracle": err, "input_gen_s": round(gen_s, 1)}))
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "max_rel_err_vs_oracle": err, "input_gen_s": round(gen_s, 1)})
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="5")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-timing", action="store_true")
-    ap.add_argument("--no-row-epilogue-variant", action="store_true",
-                    help="skip the extra timing of the same shard with the row-parallel epilogue on")
-    ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "ln", "memopt"],
-                    help="layer: tp_layer_fwd + tp_layer_bwd (the headline metric); layer-checkpoint: tp_layer_fwd + "
-                         "tp_layer_bwd_recompute; ln: replicated LayerNorm forward + backward on the config's [M, H]; "
-                         "memopt: one rank's local compute in the memory-optimised distribution at the config's widths")
-    ap.add_argument("--single-stream", action="store_true",
-                    help="time the plain schedule, every kernel on the caller's stream, instead of the two-chain "
-                         "schedule (TPL_SIDE_STREAM: the MLP block of a pass on a second, library-owned stream)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="only run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs one tensor-parallel rank's shard on ONE GPU; "
-              "--gpus above 1 is not supported (no collectives in this path)", file=sys.stderr)
-        sys.exit(2)
+def _cores():
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([i.get("num_threads", 1) for i in threadpool_info()] or [1]))
+    except Exception:
+        return os.cpu_count()
 
+
+def _rms_rel(got, ref):
     import numpy as np
-    import torch
-    import synthetic
-    import paper_2111_05972_amd as pkg
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    den = np.sqrt(np.mean(ref * ref))
+    return float(np.sqrt(np.mean((got - ref) ** 2)) / den) if den > 0 else 0.0
 
-    pkg.load_library()   # raises if the HIP library is missing: there is no fallback
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    if args.calibrate_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
-        return
-    key = int(args.config) if args.config.isdigit() else args.config
-    cfg = synthetic.get_config(key)
-    dt = pkg.TPL_F32 if cfg.dtype == "f32" else pkg.TPL_BF16
+
+def bench_layer(args, cfg, dt, pkg, torch, synthetic, ckpt=False, extras=True, oracle_limit=3.0e12, graph=False):
+    """tp_layer_fwd + tp_layer_bwd (or tp_layer_bwd_recompute) on one config; returns the result as a dict.
+
+    extras: also time the plain single-stream schedule, the row-epilogue variant and each GEMM launch (headline run).
+    oracle_limit: the oracle runs on the full workload when its model flops are below this, else on a quarter of
+    the tokens (timing only, no error figure).  graph: also capture fwd + bwd into a HIP graph and time replays."""
     peak = F32_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_PEAK_TFLOPS
-    if args.workload == "ln":
-        return bench_layernorm(args, cfg, dt, pkg, torch, synthetic)
-    if args.workload == "memopt":
-        return bench_memopt(args, cfg, dt, pkg, torch, synthetic)
-
     t0 = time.time()
     d = synthetic.make_inputs(cfg)
     host_sh = pkg.shard_params(d, cfg.tp_degree if cfg.global_params else 1,
                                cfg.tp_rank if cfg.global_params else 0)
-    layer = pkg.TpLayer(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt,
-                        cfg.causal, cfg.row_epilogue, cfg.head_dim, cfg.intermediate, side_stream=not args.single_stream)
+    mk_layer = lambda side, epi=cfg.row_epilogue: pkg.TpLayer(  # noqa: E731
+        cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt, cfg.causal, epi,
+        cfg.head_dim, cfg.intermediate, side_stream=side)
+    layer = mk_layer(not args.single_stream)
     p = {k: pkg.to_device(v, dt) for k, v in host_sh.items()}
     x = {k: pkg.to_device(d[k], dt) for k in ("x_a", "x_m", "dy_a", "dy_m")}
     y_a, y_m = layer.empty_outputs()
@@ -281,32 +256,20 @@ def main():
     grads = layer.empty_grads()
     stream = torch.cuda.current_stream()
     gen_s = time.time() - t0
-
-    ckpt = args.workload == "layer-checkpoint"
     ws_ckpt = torch.empty(pkg.tp_layer_workspace_bytes_recompute(layer.desc), dtype=torch.uint8,
                           device="cuda") if ckpt else None
 
-    def step():
-        layer.forward(p, x["x_a"], x["x_m"], y_a, y_m, stream=stream)
-        if ckpt:    # backward recomputes QKV, O, LSE, U, G from the block inputs instead of reading `saved`
-            pkg.tp_layer_bwd_recompute(layer.desc, p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m,
-                                       ws_ckpt, stream=stream)
-        else:
-            layer.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m, stream=stream)
+    def make_step(lay, g=grads):
+        def step():
+            lay.forward(p, x["x_a"], x["x_m"], y_a, y_m, stream=stream)
+            if ckpt:    # backward recomputes QKV, O, LSE, U, G from the block inputs instead of reading `saved`
+                pkg.tp_layer_bwd_recompute(lay.desc, p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], g, dx_a, dx_m,
+                                           ws_ckpt, stream=stream)
+            else:
+                lay.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], g, dx_a, dx_m, stream=stream)
+        return step
+    step = make_step(layer)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t1
-    ms_per_step = 1e3 * elapsed / args.steps
-    f_fwd, f_bwd = cfg.flops()
-    tflops = (f_fwd + f_bwd) / (ms_per_step * 1e-3) / 1e12
-
-    # fwd / bwd split with events on the launch stream
     def timed(fn, n):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
@@ -315,36 +278,62 @@ def main():
         e1.record(stream)
         e1.synchronize()
         return e0.elapsed_time(e1) / n
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = 1e3 * (time.perf_counter() - t1) / args.steps
+    f_fwd, f_bwd = cfg.flops()
+    tflops = (f_fwd + f_bwd) / (ms_per_step * 1e-3) / 1e12
     n_split = max(3, min(args.steps, 10))
     fwd_ms = timed(lambda: layer.forward(p, x["x_a"], x["x_m"], y_a, y_m, stream=stream), n_split)
-    bwd_ms = timed(lambda: layer.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m,
-                                          stream=stream), n_split)
+    out = {
+        "metric": "TFLOP/s (fwd+bwd) per TP-rank layer shard on 1 MI355X; % bf16 MFMA peak",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "pct_of_peak": round(100.0 * tflops / peak, 2), "peak_tflops": peak,
+        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(ms_per_step - fwd_ms, 4),
+        "config": {"workload": f"config {cfg.cfg_id}: {cfg.name}" + (" (activation-checkpoint backward)" if ckpt else ""),
+                   "hidden": cfg.hidden, "heads": cfg.heads, "head_dim": cfg.head_dim, "tp_degree": cfg.tp_degree,
+                   "tp_rank": cfg.tp_rank, "seq": cfg.seq, "micro_batch": cfg.micro_batch, "causal": cfg.causal,
+                   "row_epilogue": cfg.row_epilogue, "model_tflop_per_step": round((f_fwd + f_bwd) / 1e12, 4),
+                   "schedule": "one stream" if args.single_stream else "two chains (TPL_SIDE_STREAM)",
+                   "params": "shard generated directly" if not cfg.global_params else "sliced from unsharded"},
+    }
 
+    # A/B of the schedule: the same step with every kernel on the caller's stream
+    if extras and not args.single_stream:
+        lay1 = mk_layer(False)
+        s1 = make_step(lay1)
+        s1(); s1()
+        one_ms = timed(s1, n_split)
+        out["single_stream"] = {"ms_per_step": round(one_ms, 4), "value": round((f_fwd + f_bwd) / (one_ms * 1e-3) / 1e12, 2),
+                                "steps": n_split, "what": "the same step without TPL_SIDE_STREAM (every kernel on the caller's stream)"}
+        del lay1
     # the same shard with the row-parallel epilogue on (bias + residual in the two row-parallel GEMMs, residual
     # gradients in the two input-gradient GEMMs, db_o and db_dn): the headline rank runs with it off
-    flag_on = None
-    if not cfg.row_epilogue and not ckpt and not args.no_row_epilogue_variant:
-        layer_on = pkg.TpLayer(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt,
-                               cfg.causal, True, cfg.head_dim, cfg.intermediate)
+    if extras and not cfg.row_epilogue and not ckpt and not args.no_row_epilogue_variant:
+        layer_on = mk_layer(not args.single_stream, True)
         grads_on = layer_on.empty_grads()
-
-        def step_on():
-            layer_on.forward(p, x["x_a"], x["x_m"], y_a, y_m, stream=stream)
-            layer_on.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads_on, dx_a, dx_m, stream=stream)
-        step_on()
-        step_on()
+        step_on = make_step(layer_on, grads_on)
+        step_on(); step_on()
         on_ms = timed(step_on, n_split)
-        flag_on = {"ms_per_step": round(on_ms, 4), "value": round((f_fwd + f_bwd) / (on_ms * 1e-3) / 1e12, 2),
-                   "steps": n_split, "what": "same shard with the bias + residual epilogue of the row-parallel GEMMs on"}
+        out["row_epilogue_on"] = {"ms_per_step": round(on_ms, 4), "value": round((f_fwd + f_bwd) / (on_ms * 1e-3) / 1e12, 2),
+                                  "steps": n_split, "what": "same shard with the bias + residual epilogue of the row-parallel GEMMs on"}
         del layer_on, grads_on
 
     # dominant kernel: the GEMM kernel.  Its 12 launches per step are timed inside real steps: the
     # library brackets each GEMM launch with HIP events on the launch stream (tp_layer_profile).
     roofline = None
     if not args.no_kernel_timing:
-        names = [g[0] for g in gemm_list(cfg)]
-        flops = {g[0]: 2.0 * g[3] * g[4] * g[5] for g in gemm_list(cfg)}
-        shapes = {g[0]: {"M": g[3], "N": g[4], "K": g[5]} for g in gemm_list(cfg)}
+        names = [g_[0] for g_ in gemm_list(cfg)]
+        flops = {g_[0]: 2.0 * g_[3] * g_[4] * g_[5] for g_ in gemm_list(cfg)}
+        shapes = {g_[0]: {"M": g_[3], "N": g_[4], "K": g_[5]} for g_ in gemm_list(cfg)}
         reps = max(3, min(args.steps, 10))
         pkg.tp_layer_profile(1)
         for _ in range(reps):
@@ -371,65 +360,171 @@ def main():
                 traffic = json.load(open(tpath)).get(cfg.name, {}).get("bytes_per_launch")
             except Exception:
                 traffic = None
-        launches = {n: {**shapes[n], "ms": round(per[n], 4), "tflops": round(flops[n] / per[n] / 1e9, 1)} for n in names}
         roofline = {"kernel": "bf16 MFMA GEMM kernels of gemm_bf16.hip (12 launches per step, one at a time)" if cfg.dtype == "bf16" else "gemm_simple_kernel",
                     "bound": "mfma" if cfg.dtype == "bf16" else "alu",
                     "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                     "frac": round(achieved / peak, 4), "traffic": traffic,
                     "flops_per_launch": tot_fl / 12, "avg_launch_ms": round(tot_ms / 12, 4),
-                    "gemm_ms_per_step": round(tot_ms, 4), "launches": launches}
+                    "gemm_ms_per_step": round(tot_ms, 4)}
+        if extras:
+            roofline["launches"] = {n: {**shapes[n], "ms": round(per[n], 4), "tflops": round(flops[n] / per[n] / 1e9, 1)} for n in names}
+    out["roofline"] = roofline
 
-    cpu_baseline = None
-    max_err = None
+    cpu_baseline, max_err, rms_err = None, None, None
     if not args.no_cpu_baseline:
         import oracle
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-        except Exception:
-            cores = os.cpu_count()
-        # bounded sample: the full workload if it is small enough, else the same widths on fewer tokens
         from synthetic.configs import small_variant
         scfg, sample = cfg, "full workload, one fwd+bwd pass"
-        if sum(cfg.flops()) > 3.0e12:
+        if sum(cfg.flops()) > oracle_limit:
             scfg = small_variant(cfg, seq=max(1, cfg.seq // 4))
             sample = f"same widths, seq {scfg.seq} (1/4 of the tokens), one fwd+bwd pass"
-        if scfg is cfg:
-            sd, ssh = d, host_sh
-        else:
-            sd = {k: (v[:scfg.tokens] if k in ("x_a", "x_m", "dy_a", "dy_m") else v) for k, v in d.items()}
-            ssh = host_sh
+        sd = d if scfg is cfg else {k: (v[:scfg.tokens] if k in ("x_a", "x_m", "dy_a", "dy_m") else v) for k, v in d.items()}
+        # the oracle shards with its own rule (the product sharded the GPU side above)
+        osh = oracle.shard_params(d, cfg.tp_degree if cfg.global_params else 1, cfg.tp_rank if cfg.global_params else 0)
         a = (scfg.micro_batch, scfg.seq, scfg.local_heads, scfg.head_dim, scfg.causal, scfg.row_epilogue)
         c0 = time.perf_counter()
-        ya, ym, osv = oracle.layer_fwd(sd["x_a"], sd["x_m"], ssh, *a)
-        ref = oracle.layer_bwd(sd["x_a"], sd["x_m"], ssh, sd["dy_a"], sd["dy_m"], osv, *a)
+        ya, ym, osv = oracle.layer_fwd(sd["x_a"], sd["x_m"], osh, *a)
+        ref = oracle.layer_bwd(sd["x_a"], sd["x_m"], osh, sd["dy_a"], sd["dy_m"], osv, *a)
         cpu_s = time.perf_counter() - c0
-        cpu_baseline = {"value": round(sum(scfg.flops()) / cpu_s / 1e12, 4), "unit": "TFLOP/s", "cores": int(cores),
+        cpu_baseline = {"value": round(sum(scfg.flops()) / cpu_s / 1e12, 4), "unit": "TFLOP/s", "cores": _cores(),
                         "kind": "oracle", "sample": sample, "seconds": round(cpu_s, 2)}
         if scfg is cfg:
             ref.update(y_a=ya, y_m=ym)
             got = {"y_a": y_a, "y_m": y_m, "dx_a": dx_a, "dx_m": dx_m, **grads}
             step()
             torch.cuda.synchronize()
-            max_err = max(oracle.max_rel_err(v.float().cpu().numpy(), ref[k]) for k, v in got.items() if k in ref)
+            host = {k: v.float().cpu().numpy() for k, v in got.items() if k in ref}
+            max_err = max(oracle.max_rel_err(v, ref[k]) for k, v in host.items())
+            rms_err = max(_rms_rel(v, ref[k]) for k, v in host.items())
+    out.update(cpu_baseline=cpu_baseline, max_rel_err_vs_oracle=max_err, rms_rel_err_vs_oracle=rms_err,
+               input_gen_s=round(gen_s, 1))
+    # the step captured by the caller into a HIP graph and replayed (launch-bound shapes)
+    if graph and not ckpt:
+        try:
+            side = torch.cuda.Stream()
+            g = torch.cuda.CUDAGraph()
+            side.wait_stream(stream)
+            with torch.cuda.stream(side):
+                cap_stream = torch.cuda.current_stream()
 
-    out = {
-        "metric": "TFLOP/s (fwd+bwd) per TP-rank layer shard on 1 MI355X; % bf16 MFMA peak",
-        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype, "data": "synthetic",
-        "pct_of_peak": round(100.0 * tflops / peak, 2), "peak_tflops": peak,
-        "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
-        "config": {"workload": f"config {cfg.cfg_id}: {cfg.name}" + (" (activation-checkpoint backward)" if ckpt else ""), "hidden": cfg.hidden, "heads": cfg.heads,
-                   "head_dim": cfg.head_dim, "tp_degree": cfg.tp_degree, "tp_rank": cfg.tp_rank, "seq": cfg.seq,
-                   "micro_batch": cfg.micro_batch, "causal": cfg.causal, "row_epilogue": cfg.row_epilogue,
-                   "model_tflop_per_step": round((f_fwd + f_bwd) / 1e12, 4),
-                   "params": "shard generated directly" if not cfg.global_params else "sliced from unsharded"},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "max_rel_err_vs_oracle": max_err,
-        "input_gen_s": round(gen_s, 1),
-    }
-    if flag_on is not None:
-        out["row_epilogue_on"] = flag_on
+                def cap_step():
+                    layer.forward(p, x["x_a"], x["x_m"], y_a, y_m, stream=cap_stream)
+                    layer.backward(p, x["x_a"], x["x_m"], x["dy_a"], x["dy_m"], grads, dx_a, dx_m, stream=cap_stream)
+                cap_step()
+                torch.cuda.synchronize()
+                with torch.cuda.graph(g, stream=side):
+                    cap_step()
+            stream.wait_stream(side)
+            for _ in range(3):
+                g.replay()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                g.replay()
+            torch.cuda.synchronize()
+            gms = 1e3 * (time.perf_counter() - t1) / args.steps
+            out["graph_replay"] = {"ms_per_step": round(gms, 4), "value": round((f_fwd + f_bwd) / (gms * 1e-3) / 1e12, 2),
+                                   "what": "tp_layer_fwd + tp_layer_bwd captured by the caller into one HIP graph, replayed"}
+        except Exception as e:      # capture is the caller's business; the eager figure stands
+            out["graph_replay"] = {"error": str(e)[:200]}
+
+    return out
+
+
+def _brief(r):
+    """One workload's result cut down to what the `other_workloads` block carries."""
+    keep = ("metric", "value", "unit", "ms_per_step", "dtype", "pct_of_peak", "fwd_ms", "bwd_ms", "max_rel_err_vs_oracle",
+            "rms_rel_err_vs_oracle", "single_stream", "graph_replay")
+    b = {k: r[k] for k in keep if k in r and r[k] is not None}
+    b["workload"] = r["config"]["workload"]
+    if r.get("roofline"):
+        b["roofline"] = {k: r["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac") if k in r["roofline"]}
+    if r.get("cpu_baseline"):
+        b["cpu_baseline"] = {k: r["cpu_baseline"][k] for k in ("value", "unit", "cores", "sample", "seconds") if k in r["cpu_baseline"]}
+    return b
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-row-epilogue-variant", action="store_true",
+                    help="skip the extra timing of the same shard with the row-parallel epilogue on")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="only the headline workload: skip the `other_workloads` block of the default run")
+    ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "ln", "memopt"],
+                    help="layer: tp_layer_fwd + tp_layer_bwd (the headline metric); layer-checkpoint: tp_layer_fwd + "
+                         "tp_layer_bwd_recompute; ln: replicated LayerNorm forward + backward on the config's [M, H]; "
+                         "memopt: one rank's local compute in the memory-optimised distribution at the config's widths")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="time the plain schedule, every kernel on the caller's stream, instead of the two-chain "
+                         "schedule (TPL_SIDE_STREAM: the MLP block of a pass on a second, library-owned stream)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy (reference point for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs one tensor-parallel rank's shard on ONE GPU; "
+              "--gpus above 1 is not supported (no collectives in this path)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synthetic
+    import paper_2111_05972_amd as pkg
+
+    pkg.load_library()   # raises if the HIP library is missing: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
+        return
+    key = int(args.config) if args.config.isdigit() else args.config
+    cfg = synthetic.get_config(key)
+    dt = pkg.TPL_F32 if cfg.dtype == "f32" else pkg.TPL_BF16
+    if args.workload == "ln":
+        print(json.dumps(bench_layernorm(args, cfg, dt, pkg, torch, synthetic)))
+        return
+    if args.workload == "memopt":
+        print(json.dumps(bench_memopt(args, cfg, dt, pkg, torch, synthetic)))
+        return
+    out = bench_layer(args, cfg, dt, pkg, torch, synthetic, ckpt=args.workload == "layer-checkpoint")
+
+    # The default run also carries every other configuration and workload, each measured the same way (fewer steps;
+    # the oracle on the full workload where that takes seconds), so that one line shows the whole picture.
+    default_run = args.workload == "layer" and key == 5 and not args.no_other_workloads
+    if default_run:
+        import copy
+        others = []
+        oa = copy.copy(args)
+        oa.steps, oa.warmup = max(5, min(args.steps, 20)), 3
+        t_start = time.time()
+
+        def attempt(what, fn):      # a failure here must not cost the headline line
+            torch.cuda.empty_cache()
+            try:
+                others.append(_brief(fn()))
+            except Exception as e:
+                others.append({"workload": what, "error": str(e)[:300]})
+        for k in (1, 2, 3, 4, "roberta-10b-tp4", "bert-10b-tp4"):
+            c = synthetic.get_config(k)
+            cdt = pkg.TPL_F32 if c.dtype == "f32" else pkg.TPL_BF16
+            attempt(f"config {c.cfg_id}: {c.name}", lambda c=c, cdt=cdt, k=k: bench_layer(
+                oa, c, cdt, pkg, torch, synthetic, extras=False,
+                oracle_limit=2.5e12 if time.time() - t_start < 150 else 0.0, graph=k in (1, 2, 3)))
+        attempt("layer-checkpoint", lambda: bench_layer(oa, cfg, dt, pkg, torch, synthetic, ckpt=True, extras=False,
+                                                        oracle_limit=0.0))
+        attempt("ln", lambda: bench_layernorm(oa, cfg, dt, pkg, torch, synthetic))
+        ma = copy.copy(oa)
+        ma.no_cpu_baseline = args.no_cpu_baseline or time.time() - t_start > 200
+        attempt("memopt", lambda: bench_memopt(ma, cfg, dt, pkg, torch, synthetic))
+        out["other_workloads"] = others
     print(json.dumps(out))
 
 
