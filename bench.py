@@ -431,6 +431,89 @@ def bench_layer(args, cfg, dt, pkg, torch, synthetic, ckpt=False, extras=True, o
     return out
 
 
+def bench_gemms(args, cfg, dt, pkg, torch, synthetic):
+    """The 12 GEMMs of a step, each alone in a sustained loop on random operands: this library (tp_layer_gemm) and,
+    as a reference point of what the chip sustains on the same shape, the vendor library behind torch.matmul.  Two
+    regimes: `hot` (the same operands every launch: they stay in the 256 MB infinity cache) and `cold` (four operand
+    sets in rotation, more than the cache holds, as inside a layer step where every weight is read once).  A host
+    thread samples board power and core clock from sysfs during the hot loop (the GEMMs run at the power limit)."""
+    import glob
+    import threading
+    st = torch.cuda.current_stream()
+    hw = {}
+    for h in glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*"):
+        if os.path.exists(os.path.join(h, "power1_input")):
+            hw.setdefault("power", os.path.join(h, "power1_input"))
+    for q in glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"):
+        hw.setdefault("sclk", q)
+
+    def sample(stop, acc):
+        while not stop.is_set():
+            try:
+                if "power" in hw:
+                    acc["w"].append(float(open(hw["power"]).read()) / 1e6)
+                if "sclk" in hw:
+                    cur = [l for l in open(hw["sclk"]).read().splitlines() if "*" in l]
+                    if cur:
+                        acc["mhz"].append(float(cur[0].split(":")[1].lower().replace("mhz", "").replace("*", "").strip()))
+            except Exception:
+                pass
+            time.sleep(0.05)
+
+    def loop(fn, secs, sampled):
+        for i in range(6):
+            fn(i)
+        torch.cuda.synchronize()
+        stop, acc = threading.Event(), {"w": [], "mhz": []}
+        th = threading.Thread(target=sample, args=(stop, acc)) if sampled else None
+        if th:
+            th.start()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0, n = time.time(), 0
+        e0.record(st)
+        while time.time() - t0 < secs:
+            for i in range(40):
+                fn(n + i)
+            n += 40
+            torch.cuda.synchronize()
+        e1.record(st)
+        e1.synchronize()
+        stop.set()
+        if th:
+            th.join()
+        half = lambda v: v[len(v) // 2:]   # noqa: E731
+        avg = lambda v: round(sum(half(v)) / len(half(v)), 1) if v else None   # noqa: E731
+        return e0.elapsed_time(e1) / n, avg(acc["w"]), avg(acc["mhz"])
+    rows = {}
+    secs = 0.6 if args.steps <= 30 else 1.5
+    for name, ta, tb, M, N, K in gemm_list(cfg):
+        nrot = 4
+        As = [torch.randn((K, M) if ta else (M, K), device="cuda", dtype=torch.bfloat16) for _ in range(nrot)]
+        Bs = [torch.randn((N, K) if tb else (K, N), device="cuda", dtype=torch.bfloat16) for _ in range(nrot)]
+        C = torch.empty(M, N, device="cuda", dtype=torch.bfloat16)
+        ws = torch.empty(max(256, pkg.tp_layer_gemm_workspace_bytes(dt, M, N, K)), dtype=torch.uint8, device="cuda")
+        ours = lambda i, r: pkg.tp_layer_gemm(dt, ta, tb, M, N, K, As[i % r], Bs[i % r], C, ws=ws, stream=st)   # noqa: E731
+        vend = lambda i, r: torch.matmul(As[i % r].t() if ta else As[i % r], Bs[i % r].t() if tb else Bs[i % r], out=C)   # noqa: E731
+        fl = 2.0 * M * N * K
+        row = {"M": M, "N": N, "K": K, "layout": ("T" if ta else "N") + ("T" if tb else "N")}
+        for who, f in (("ours", ours), ("vendor", vend)):
+            hot_ms, w, mhz = loop(lambda i: f(i, 1), secs, True)
+            cold_ms, _, _ = loop(lambda i: f(i, nrot), secs, False)
+            row[who] = {"hot_tflops": round(fl / hot_ms / 1e9, 1), "cold_tflops": round(fl / cold_ms / 1e9, 1),
+                        "hot_watts": w, "hot_mhz": mhz}
+        rows[name] = row
+        del As, Bs, C
+        torch.cuda.empty_cache()
+    tot = lambda who, k: sum(2.0 * r["M"] * r["N"] * r["K"] for r in rows.values()) / sum(   # noqa: E731
+        2.0 * r["M"] * r["N"] * r["K"] / r[who][k] for r in rows.values())
+    return {"metric": "TFLOP/s of each GEMM of a step alone, sustained loop, random operands", "unit": "TFLOP/s",
+            "value": round(tot("ours", "cold_tflops"), 1), "dtype": cfg.dtype, "data": "synthetic",
+            "config": {"workload": f"the 12 GEMMs of config {cfg.cfg_id}: {cfg.name}, one at a time"},
+            "flop_weighted": {who: {k: round(tot(who, k), 1) for k in ("hot_tflops", "cold_tflops")} for who in ("ours", "vendor")},
+            "vendor": "torch.matmul (hipBLASLt / rocBLAS), a reference point only: not on the product path",
+            "gemms": rows}
+
+
 def _brief(r):
     """One workload's result cut down to what the `other_workloads` block carries."""
     keep = ("metric", "value", "unit", "ms_per_step", "dtype", "pct_of_peak", "fwd_ms", "bwd_ms", "max_rel_err_vs_oracle",
@@ -456,10 +539,12 @@ def main():
                     help="skip the extra timing of the same shard with the row-parallel epilogue on")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="only the headline workload: skip the `other_workloads` block of the default run")
-    ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "ln", "memopt"],
+    ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "ln", "memopt", "gemms"],
                     help="layer: tp_layer_fwd + tp_layer_bwd (the headline metric); layer-checkpoint: tp_layer_fwd + "
                          "tp_layer_bwd_recompute; ln: replicated LayerNorm forward + backward on the config's [M, H]; "
-                         "memopt: one rank's local compute in the memory-optimised distribution at the config's widths")
+                         "memopt: one rank's local compute in the memory-optimised distribution at the config's widths; "
+                         "gemms: each GEMM of a step alone in a sustained loop, beside the vendor library on the same shape, "
+                         "with board power and clock")
     ap.add_argument("--single-stream", action="store_true",
                     help="time the plain schedule, every kernel on the caller's stream, instead of the two-chain "
                          "schedule (TPL_SIDE_STREAM: the MLP block of a pass on a second, library-owned stream)")
@@ -493,6 +578,9 @@ def main():
         return
     if args.workload == "memopt":
         print(json.dumps(bench_memopt(args, cfg, dt, pkg, torch, synthetic)))
+        return
+    if args.workload == "gemms":
+        print(json.dumps(bench_gemms(args, cfg, dt, pkg, torch, synthetic)))
         return
     out = bench_layer(args, cfg, dt, pkg, torch, synthetic, ckpt=args.workload == "layer-checkpoint")
 
