@@ -190,10 +190,49 @@ __global__ __launch_bounds__(LN_THREADS) void ln_bwd_tile_kernel(int64_t M, int6
     }
 }
 
-// Backward in one pass (replicated LayerNorm).  partials[g][0][:] = dgamma, partials[g][1][:] = dbeta of the rows
-// walked by workgroup g.
-constexpr int LN_BWD_GROUPS = 256;     // workgroups of the backward kernel = rows of its partial sums
-template <typename T, int MAXC, int THREADS>
+// Eight consecutive elements as they sit in memory (16 or 32 bytes), converted only when used: rows that are
+// still in flight cost half the registers in bfloat16.
+template <typename T> struct Raw8;
+template <> struct Raw8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const float* p) { a = reinterpret_cast<const float4*>(p)[0]; b = reinterpret_cast<const float4*>(p)[1]; }
+    __device__ __forceinline__ void get(float (&v)[8]) const {
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+};
+template <> struct Raw8<bf16_t> {
+    uint4 u;
+    __device__ __forceinline__ void load(const bf16_t* p) { u = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void get(float (&v)[8]) const {
+        const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+};
+
+// Two sums over the workgroup at once (same values returned to every thread; fixed combination order).
+template <int NW>
+__device__ __forceinline__ void block_sum2(float& a, float& b, float (*red)[NW]) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { a += __shfl_xor(a, o, 64); b += __shfl_xor(b, o, 64); }
+    const int w = threadIdx.x >> 6;
+    __syncthreads();                   // red may still be read from the previous row
+    if ((threadIdx.x & 63) == 0) { red[0][w] = a; red[1][w] = b; }
+    __syncthreads();
+    a = red[0][0];
+    b = red[1][0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) { a += red[0][i]; b += red[1][i]; }
+}
+
+// Backward in one pass (replicated LayerNorm).  Workgroup g of G walks rows g, g + G, ...; the next DEPTH rows of
+// dy and z are always in flight (unconverted, in a ring of registers: the kernel is bound by how many bytes a CU
+// keeps outstanding, not by arithmetic).  partials[g][0][:] = dgamma, partials[g][1][:] = dbeta of its rows.
+constexpr int LN_BWD_GROUPS = 256;     // most workgroups of the backward kernel = rows of its partial sums
+template <typename T, int MAXC, int THREADS, int DEPTH>
 __global__ __launch_bounds__(THREADS) void ln_bwd_fused_kernel(int64_t M, int64_t H, const T* __restrict__ dy,
                                                                   const T* __restrict__ z,
                                                                   const float* __restrict__ mean,
@@ -201,8 +240,10 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_fused_kernel(int64_t M, int64_
                                                                   const T* __restrict__ gamma,
                                                                   T* __restrict__ dz,
                                                                   float* __restrict__ partials) {
-    __shared__ float red[THREADS / 64];
+    constexpr int NW = THREADS / 64;
+    __shared__ float red[2][NW];
     const int t = threadIdx.x;
+    const int64_t G = gridDim.x;
     const float inv_h = 1.0f / (float)H;
     float gm[MAXC][8], dgam[MAXC][8], dbet[MAXC][8];
 #pragma unroll
@@ -212,52 +253,59 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_fused_kernel(int64_t M, int64_
         for (int e = 0; e < 8; ++e) { gm[i][e] = 0.0f; dgam[i][e] = 0.0f; dbet[i][e] = 0.0f; }
         if (col < H) load8(gamma + col, gm[i]);
     }
-    float g[MAXC][8], zz[MAXC][8], gn[MAXC][8], zn[MAXC][8];
-    auto fetch = [&](int64_t row, float (&a)[MAXC][8], float (&b)[MAXC][8]) {
+    Raw8<T> rg[DEPTH][MAXC], rz[DEPTH][MAXC];
+    auto fetch = [&](int64_t row, Raw8<T> (&a)[MAXC], Raw8<T> (&b)[MAXC]) {
 #pragma unroll
         for (int i = 0; i < MAXC; ++i) {
             const int64_t col = ((int64_t)t + THREADS * i) * 8;
-            if (col < H && row < M) { load8(dy + row * H + col, a[i]); load8(z + row * H + col, b[i]); }
+            if (col < H && row < M) { a[i].load(dy + row * H + col); b[i].load(z + row * H + col); }
         }
     };
-    fetch(blockIdx.x, g, zz);
-    for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
-        fetch(row + gridDim.x, gn, zn);                      // next row of this workgroup, in flight during the sums
-        const float mu = mean[row], rs = rstd[row];
-        float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
-        for (int i = 0; i < MAXC; ++i) {
-            const int64_t col = ((int64_t)t + THREADS * i) * 8;
-            if (col < H) {
+    for (int d = 0; d < DEPTH; ++d) fetch(blockIdx.x + d * G, rg[d], rz[d]);
+    for (int64_t row0 = blockIdx.x; row0 < M; row0 += DEPTH * G) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    zz[i][e] = (zz[i][e] - mu) * rs;          // zh
-                    const float gg = g[i][e] * gm[i][e];
-                    s1 += gg;
-                    s2 = fmaf(gg, zz[i][e], s2);
+        for (int d = 0; d < DEPTH; ++d) {
+            const int64_t row = row0 + d * G;
+            if (row < M) {                                     // uniform over the workgroup
+                float g[MAXC][8], zz[MAXC][8];
+#pragma unroll
+                for (int i = 0; i < MAXC; ++i) { rg[d][i].get(g[i]); rz[d][i].get(zz[i]); }
+                fetch(row + DEPTH * G, rg[d], rz[d]);          // the ring slot is free again
+                const float mu = mean[row], rs = rstd[row];
+                float c1 = 0.0f, c2 = 0.0f;
+#pragma unroll
+                for (int i = 0; i < MAXC; ++i) {
+                    const int64_t col = ((int64_t)t + THREADS * i) * 8;
+                    if (col < H) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            zz[i][e] = (zz[i][e] - mu) * rs;   // zh
+                            const float gg = g[i][e] * gm[i][e];
+                            c1 += gg;
+                            c2 = fmaf(gg, zz[i][e], c2);
+                        }
+                    }
+                }
+                block_sum2<NW>(c1, c2, red);
+                c1 *= inv_h;
+                c2 *= inv_h;
+#pragma unroll
+                for (int i = 0; i < MAXC; ++i) {
+                    const int64_t col = ((int64_t)t + THREADS * i) * 8;
+                    if (col < H) {
+                        float o[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            dbet[i][e] += g[i][e];
+                            dgam[i][e] = fmaf(g[i][e], zz[i][e], dgam[i][e]);
+                            o[e] = (g[i][e] * gm[i][e] - c1 - zz[i][e] * c2) * rs;
+                        }
+                        store8(dz + row * H + col, o);
+                    }
                 }
             }
         }
-        const float c1 = block_sum<THREADS / 64>(s1, red) * inv_h;
-        const float c2 = block_sum<THREADS / 64>(s2, red) * inv_h;
-#pragma unroll
-        for (int i = 0; i < MAXC; ++i) {
-            const int64_t col = ((int64_t)t + THREADS * i) * 8;
-            if (col < H) {
-                float o[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    dbet[i][e] += g[i][e];
-                    dgam[i][e] = fmaf(g[i][e], zz[i][e], dgam[i][e]);
-                    o[e] = (g[i][e] * gm[i][e] - c1 - zz[i][e] * c2) * rs;
-                }
-                store8(dz + row * H + col, o);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < MAXC; ++i)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { g[i][e] = gn[i][e]; zz[i][e] = zn[i][e]; }
     }
     float* pg = partials + (int64_t)blockIdx.x * 2 * H;
 #pragma unroll
@@ -268,29 +316,37 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_fused_kernel(int64_t M, int64_
 }
 
 // dgamma, dbeta = sums of the per-workgroup partials [groups][2][H], in group order within four interleaved lanes
-// that are then combined in lane order (fixed order).  64 columns x 4 group lanes per workgroup; blockIdx.y picks
-// gamma or beta.
+// that are then combined in lane order (fixed order).  A thread owns four adjacent columns (16-byte loads); 64 such
+// threads x 4 group lanes per workgroup; blockIdx.y picks gamma or beta.
 template <typename T>
 __global__ __launch_bounds__(256) void ln_sum_partials_kernel(int64_t groups, int64_t H, const float* __restrict__ part,
                                                              T* __restrict__ dgamma, T* __restrict__ dbeta) {
-    __shared__ float red[4][64];
+    __shared__ float4 red[4][64];
     const int cl = threadIdx.x & 63, gl = threadIdx.x >> 6;
-    const int64_t col = (int64_t)blockIdx.x * 64 + cl;
+    const int64_t col = ((int64_t)blockIdx.x * 64 + cl) * 4;          // H is a multiple of 8
     const float* src = part + (int64_t)blockIdx.y * H + col;
-    float s = 0.0f;
+    float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    auto add = [&](const float4& v) { s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w; };
     if (col < H) {
         int64_t g = gl;
         for (; g + 12 < groups; g += 16) {           // four independent loads in flight per thread
-            const float a = src[g * 2 * H], b = src[(g + 4) * 2 * H], c = src[(g + 8) * 2 * H], d = src[(g + 12) * 2 * H];
-            s += a; s += b; s += c; s += d;
+            const float4 a = *reinterpret_cast<const float4*>(src + g * 2 * H);
+            const float4 b = *reinterpret_cast<const float4*>(src + (g + 4) * 2 * H);
+            const float4 c = *reinterpret_cast<const float4*>(src + (g + 8) * 2 * H);
+            const float4 d = *reinterpret_cast<const float4*>(src + (g + 12) * 2 * H);
+            add(a); add(b); add(c); add(d);
         }
-        for (; g < groups; g += 4) s += src[g * 2 * H];
+        for (; g < groups; g += 4) add(*reinterpret_cast<const float4*>(src + g * 2 * H));
     }
     red[gl][cl] = s;
     __syncthreads();
     if (gl == 0 && col < H) {
-        const float v = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
-        (blockIdx.y == 0 ? dgamma : dbeta)[col] = from_f32<T>(v);
+        T* out = (blockIdx.y == 0 ? dgamma : dbeta) + col;
+        const float4 r0 = red[0][cl], r1 = red[1][cl], r2 = red[2][cl], r3 = red[3][cl];
+        out[0] = from_f32<T>(((r0.x + r1.x) + r2.x) + r3.x);
+        out[1] = from_f32<T>(((r0.y + r1.y) + r2.y) + r3.y);
+        out[2] = from_f32<T>(((r0.z + r1.z) + r2.z) + r3.z);
+        out[3] = from_f32<T>(((r0.w + r1.w) + r2.w) + r3.w);
     }
 }
 
@@ -313,17 +369,20 @@ template <typename T, int MAXC>
 static hipError_t bwd_t(const LnArgs& a) {
     float* part = a.partials;                      // [groups][2][H]
     const int64_t groups = ln_bwd_groups(a.M);
+    // Rows in flight per workgroup beyond the one being worked on.  Measured at [2048, 12288] bfloat16: 1 -> 47 us,
+    // 2 -> 41 us, 3 and 4 -> 42 us for both kernels together (the compiler drains the whole ring once per DEPTH rows).
+    constexpr int DEPTH = (sizeof(T) == 2 && MAXC <= 6) ? 2 : 1;   // the widest rows have no registers left for two
     if constexpr (MAXC > 2)
-        hipLaunchKernelGGL((ln_bwd_fused_kernel<T, MAXC / 2, 512>), dim3((unsigned)groups), dim3(512), 0, a.stream, a.M,
-                           a.H, (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma, (T*)a.dz, part);
+        hipLaunchKernelGGL((ln_bwd_fused_kernel<T, MAXC / 2, 512, DEPTH>), dim3((unsigned)groups), dim3(512), 0, a.stream,
+                           a.M, a.H, (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma, (T*)a.dz, part);
     else
-        hipLaunchKernelGGL((ln_bwd_fused_kernel<T, MAXC, LN_THREADS>), dim3((unsigned)groups), dim3(LN_THREADS), 0,
+        hipLaunchKernelGGL((ln_bwd_fused_kernel<T, MAXC, LN_THREADS, DEPTH>), dim3((unsigned)groups), dim3(LN_THREADS), 0,
                            a.stream, a.M, a.H, (const T*)a.dy, (const T*)a.z, a.mean, a.rstd, (const T*)a.gamma,
                            (T*)a.dz, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((ln_sum_partials_kernel<T>), dim3((unsigned)((a.H + 63) / 64), 2), dim3(256), 0, a.stream, groups,
-                       a.H, part, (T*)a.dgamma, (T*)a.dbeta);
+    hipLaunchKernelGGL((ln_sum_partials_kernel<T>), dim3((unsigned)((a.H / 4 + 63) / 64), 2), dim3(256), 0, a.stream,
+                       groups, a.H, part, (T*)a.dgamma, (T*)a.dbeta);
     return hipGetLastError();
 }
 
