@@ -291,6 +291,9 @@ int tp_layer_profile_read(float* ms_out, int capacity, int* count);
  *   "gemm_band"   force the band height of the GEMM tile order
  *   "gemm_force"  "MxNxK@ab=v[:shares];..." plans for single shapes (a, b = 1 where A, B has K contiguous)
  *   "attn_chunk"  chunk length of attention strips in 64-row tile steps (0: never cut)
+ *   "fuse_colsum" 1: the bias gradients db_qkv, db_up are one more output row of the weight-gradient GEMM whenever
+ *                 its kernel supports that; 0 (default): they come from the column-sum kernels (measured inside the
+ *                 whole step the two are equal on one stream and the fused form is 0.4 % slower on two chains)
  * value: decimal text; NULL or "" returns the option to "let the library choose".  TPL_EINVAL for an unknown
  * name or a value that does not parse. */
 int tp_layer_set_option(const char* name, const char* value);

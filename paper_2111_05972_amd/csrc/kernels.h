@@ -17,11 +17,12 @@ struct Options {
     int gemm_shares = 0;       // force a K split; 0: the planner chooses
     int gemm_band = 0;         // force the band height of the tile order; 0: choose_band
     int attn_chunk = -1;       // force the chunk length of attention strips in 64-row tile steps (0: never cut); -1: unset
+    int fuse_colsum = 0;       // 1: bias gradients as one more output row of the weight-gradient GEMM where its kernel can
     char gemm_force[1024] = "";   // "MxNxK@ab=v[:shares];..." plans of single shapes (a, b = 1: A, B K-major)
     unsigned generation = 0;
 };
 const Options& options();
-// name: "gemm_tile", "gemm_shares", "gemm_band", "gemm_force", "attn_chunk"; value null or "": back to unset.
+// name: "gemm_tile", "gemm_shares", "gemm_band", "gemm_force", "attn_chunk", "fuse_colsum"; value null or "": back to unset.
 // Returns false for an unknown name or a value that does not parse.
 bool set_option(const char* name, const char* value);
 enum Epi { EPI_NONE = 0, EPI_GELU = 1, EPI_DGELU = 2 };
@@ -42,6 +43,9 @@ struct GemmArgs {
     size_t ws_bytes;
     hipStream_t stream;
     bool c_streaming;   // C is not read again soon (weight gradients): store it with the non-temporal hint
+    void* colsum_b;     // [N] or null: where the kernel may also leave sum_k B[k][n] (the bias gradient that goes with a
+                        // weight gradient); whether it did is reported by gemm_bf16 / run through colsum_done
+    bool colsum_done;
 };
 
 struct AttnArgs {
@@ -116,7 +120,7 @@ hipError_t gelu_bwd(int dtype, int64_t M, int64_t N, const void* dg, const void*
 // bf16 MFMA kernels for gfx950.
 bool gemm_bf16_supported(const GemmArgs& a);
 size_t gemm_bf16_workspace_bytes(int64_t M, int64_t N, int64_t K);
-hipError_t gemm_bf16(const GemmArgs& a);
+hipError_t gemm_bf16(const GemmArgs& a, bool* colsum_done = nullptr);
 bool attn_bf16_supported(const AttnArgs& a);
 hipError_t attn_bf16_fwd(const AttnArgs& a);
 hipError_t attn_bf16_bwd(const AttnArgs& a);

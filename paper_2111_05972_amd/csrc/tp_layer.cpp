@@ -43,6 +43,7 @@ bool set_option(const char* name, const char* value) {
     else if (!strcmp(name, "gemm_shares")) ok = parse_int(value, 0, 0, 64, &o.gemm_shares);
     else if (!strcmp(name, "gemm_band")) ok = parse_int(value, 0, 0, 1 << 20, &o.gemm_band);
     else if (!strcmp(name, "attn_chunk")) ok = parse_int(value, -1, 0, 1 << 16, &o.attn_chunk);
+    else if (!strcmp(name, "fuse_colsum")) ok = parse_int(value, 0, 0, 1, &o.fuse_colsum);
     else if (!strcmp(name, "gemm_force")) {
         const char* v = value ? value : "";
         if (strlen(v) < sizeof(o.gemm_force)) { strcpy(o.gemm_force, v); ok = true; }
@@ -227,7 +228,8 @@ int run_gemm(GemmArgs& g) {
         }
         if (hipEventRecord(g_prof.start[slot], g.stream) != hipSuccess) return TPL_EHIP;
     }
-    if (g.dtype == BF16 && gemm_bf16_supported(g)) e = gemm_bf16(g);
+    g.colsum_done = false;
+    if (g.dtype == BF16 && gemm_bf16_supported(g)) e = gemm_bf16(g, &g.colsum_done);
     else e = gemm_simple(g);
     if (slot >= 0 && hipEventRecord(g_prof.stop[slot], g.stream) != hipSuccess) return TPL_EHIP;
     return e == hipSuccess ? TPL_OK : TPL_EHIP;
@@ -349,8 +351,9 @@ int bwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
     if ((rc = run_gemm(w5))) return rc;
     GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, sc2);
     w4.c_streaming = true;
+    w4.colsum_b = gr->db_up;                 // db_up = column sums of dU: one more output row of this GEMM where it can
     if ((rc = run_gemm(w4))) return rc;
-    if (colsum(x.dtype, x.M, x.Il, du, gr->db_up, cs2, s2) != hipSuccess) return TPL_EHIP;
+    if (!w4.colsum_done && colsum(x.dtype, x.M, x.Il, du, gr->db_up, cs2, s2) != hipSuccess) return TPL_EHIP;
     GemmArgs d4 = mk(x, 0, 1, x.M, x.H, x.Il, du, p->w_up, dx_mlp, sc2);
     if (x.row_epi) d4.resid = dy_mlp;
     if ((rc = run_gemm(d4))) return rc;
@@ -372,8 +375,9 @@ int bwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
     if ((rc = run_attn(at, true))) return rc;
     GemmArgs w1 = mk(x, 1, 0, x.H, 3 * x.Hl, x.M, x_attn, dqkv, gr->dw_qkv, sc);
     w1.c_streaming = true;
+    w1.colsum_b = gr->db_qkv;
     if ((rc = run_gemm(w1))) return rc;
-    if (colsum(x.dtype, x.M, 3 * x.Hl, dqkv, gr->db_qkv, cs, s) != hipSuccess) return TPL_EHIP;
+    if (!w1.colsum_done && colsum(x.dtype, x.M, 3 * x.Hl, dqkv, gr->db_qkv, cs, s) != hipSuccess) return TPL_EHIP;
     GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, sc);
     if (x.row_epi) d1.resid = dy_attn;
     if ((rc = run_gemm(d1))) return rc;

@@ -86,6 +86,23 @@ def test_attention_strips_cut_into_chunks(chunk, tune):
         assert np.array_equal(a[k], b[k]), k
 
 
+@pytest.mark.parametrize("fuse", ["1", "0"])
+def test_bias_gradients_inside_the_weight_gradient_gemm(fuse, tune):
+    """db_qkv and db_up as one more output row of the weight-gradient GEMM (the 192 x 192 kernel forced for every
+    GEMM so that small ragged shapes take that path: N = 1560 and 2064 are no multiples of the tile, the token count
+    600 is no multiple of the k-step), and the same layer with the column-sum kernels instead; both against the
+    oracle, and the fused result twice over bit-identical."""
+    tune.set("gemm_tile", "7")
+    tune.set("fuse_colsum", fuse)
+    cfg = small_variant(C[2], name="bf16-colsum-in-wgrad", hidden=520, heads=5, head_dim=104, intermediate=2064,
+                        tp_degree=1, tp_rank=0, seq=300, micro_batch=2, causal=True, row_epilogue=True)
+    _run(cfg)
+    d, sh = shard_inputs(cfg)
+    a, b = gpu_outputs(cfg, d, sh, repeat=2)
+    for k in ("db_qkv", "db_up"):
+        assert np.array_equal(a[k], b[k]), k
+
+
 def test_run_to_run_determinism():
     cfg = SMALL[3]
     d, sh = shard_inputs(cfg)
