@@ -315,38 +315,40 @@ __global__ __launch_bounds__(THREADS) void ln_bwd_fused_kernel(int64_t M, int64_
     }
 }
 
-// dgamma, dbeta = sums of the per-workgroup partials [groups][2][H], in group order within four interleaved lanes
-// that are then combined in lane order (fixed order).  A thread owns four adjacent columns (16-byte loads); 64 such
-// threads x 4 group lanes per workgroup; blockIdx.y picks gamma or beta.
+// dgamma, dbeta = sums of the per-workgroup partials [groups][2][H]: group lane g of 16 adds groups g, g + 16, ... in
+// order, then the 16 lanes are combined in lane order (fixed order).  A thread owns four adjacent columns (16-byte
+// loads); 16 such threads x 16 group lanes per workgroup, so that [256][2][12288] is spread over 384 workgroups;
+// blockIdx.y picks gamma or beta.
+constexpr int LN_SUM_LANES = 16, LN_SUM_COLS = 256 / LN_SUM_LANES * 4;     // columns per workgroup
 template <typename T>
 __global__ __launch_bounds__(256) void ln_sum_partials_kernel(int64_t groups, int64_t H, const float* __restrict__ part,
                                                              T* __restrict__ dgamma, T* __restrict__ dbeta) {
-    __shared__ float4 red[4][64];
-    const int cl = threadIdx.x & 63, gl = threadIdx.x >> 6;
-    const int64_t col = ((int64_t)blockIdx.x * 64 + cl) * 4;          // H is a multiple of 8
+    constexpr int CT = 256 / LN_SUM_LANES;                            // column threads
+    __shared__ float4 red[LN_SUM_LANES][CT];
+    const int cl = threadIdx.x % CT, gl = threadIdx.x / CT;
+    const int64_t col = ((int64_t)blockIdx.x * CT + cl) * 4;          // H is a multiple of 8
     const float* src = part + (int64_t)blockIdx.y * H + col;
     float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     auto add = [&](const float4& v) { s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w; };
     if (col < H) {
         int64_t g = gl;
-        for (; g + 12 < groups; g += 16) {           // four independent loads in flight per thread
+        for (; g + 3 * LN_SUM_LANES < groups; g += 4 * LN_SUM_LANES) {   // four independent loads in flight per thread
             const float4 a = *reinterpret_cast<const float4*>(src + g * 2 * H);
-            const float4 b = *reinterpret_cast<const float4*>(src + (g + 4) * 2 * H);
-            const float4 c = *reinterpret_cast<const float4*>(src + (g + 8) * 2 * H);
-            const float4 d = *reinterpret_cast<const float4*>(src + (g + 12) * 2 * H);
+            const float4 b = *reinterpret_cast<const float4*>(src + (g + LN_SUM_LANES) * 2 * H);
+            const float4 c = *reinterpret_cast<const float4*>(src + (g + 2 * LN_SUM_LANES) * 2 * H);
+            const float4 d = *reinterpret_cast<const float4*>(src + (g + 3 * LN_SUM_LANES) * 2 * H);
             add(a); add(b); add(c); add(d);
         }
-        for (; g < groups; g += 4) add(*reinterpret_cast<const float4*>(src + g * 2 * H));
+        for (; g < groups; g += LN_SUM_LANES) add(*reinterpret_cast<const float4*>(src + g * 2 * H));
     }
     red[gl][cl] = s;
     __syncthreads();
     if (gl == 0 && col < H) {
+        float4 r = red[0][cl];
+#pragma unroll
+        for (int i = 1; i < LN_SUM_LANES; ++i) { const float4 v = red[i][cl]; r.x += v.x; r.y += v.y; r.z += v.z; r.w += v.w; }
         T* out = (blockIdx.y == 0 ? dgamma : dbeta) + col;
-        const float4 r0 = red[0][cl], r1 = red[1][cl], r2 = red[2][cl], r3 = red[3][cl];
-        out[0] = from_f32<T>(((r0.x + r1.x) + r2.x) + r3.x);
-        out[1] = from_f32<T>(((r0.y + r1.y) + r2.y) + r3.y);
-        out[2] = from_f32<T>(((r0.z + r1.z) + r2.z) + r3.z);
-        out[3] = from_f32<T>(((r0.w + r1.w) + r2.w) + r3.w);
+        out[0] = from_f32<T>(r.x); out[1] = from_f32<T>(r.y); out[2] = from_f32<T>(r.z); out[3] = from_f32<T>(r.w);
     }
 }
 
@@ -381,7 +383,7 @@ static hipError_t bwd_t(const LnArgs& a) {
                            (T*)a.dz, part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((ln_sum_partials_kernel<T>), dim3((unsigned)((a.H / 4 + 63) / 64), 2), dim3(256), 0, a.stream,
+    hipLaunchKernelGGL((ln_sum_partials_kernel<T>), dim3((unsigned)((a.H + LN_SUM_COLS - 1) / LN_SUM_COLS), 2), dim3(256), 0, a.stream,
                        groups, a.H, part, (T*)a.dgamma, (T*)a.dbeta);
     return hipGetLastError();
 }
