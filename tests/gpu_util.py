@@ -34,15 +34,16 @@ def oracle_outputs(cfg, d, sh):
     return ref
 
 
-def gpu_outputs(cfg, d, sh=None, repeat=1):
+def gpu_outputs(cfg, d, sh=None, repeat=1, side_stream=False):
     """Runs the HIP path.  The parameters are sharded by the product's own rule; `sh` (the oracle's shard) is
-    accepted for the callers' convenience and not used on this side."""
+    accepted for the callers' convenience and not used on this side.  side_stream: the two-chain schedule
+    (TPL_SIDE_STREAM), which is what bench.py times."""
     import torch
     import paper_2111_05972_amd as pkg
     sh = product_shard(cfg, d)
     dt = pkg.TPL_F32 if cfg.dtype == "f32" else pkg.TPL_BF16
     layer = pkg.TpLayer(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt,
-                        cfg.causal, cfg.row_epilogue, cfg.head_dim, cfg.intermediate)
+                        cfg.causal, cfg.row_epilogue, cfg.head_dim, cfg.intermediate, side_stream=side_stream)
     p = {k: pkg.to_device(v, dt) for k, v in sh.items()}
     x = {k: pkg.to_device(d[k], dt) for k in ("x_a", "x_m", "dy_a", "dy_m")}
     runs = []

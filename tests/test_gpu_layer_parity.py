@@ -61,6 +61,21 @@ def test_named_configs_full_size(cid):
     _run(C[cid])
 
 
+@pytest.mark.parametrize("cid", [2, 3, 4, 5])
+def test_two_chain_schedule_at_full_size(cid):
+    """The launch configuration bench.py times: the attention block and the MLP block of a pass on two streams
+    (TPL_SIDE_STREAM).  Element by element against the oracle, and bit-identical to the one-stream schedule (the
+    kernels and their order within a chain are the same; only what runs beside what changes)."""
+    cfg = C[cid]
+    print(f"\n[case] two chains, {cfg.name}", flush=True)
+    d, sh = shard_inputs(cfg)
+    two = gpu_outputs(cfg, d, sh, side_stream=True)
+    compare(cfg, two, oracle_outputs(cfg, d, sh))
+    one = gpu_outputs(cfg, d, sh)
+    for k in one:
+        assert np.array_equal(one[k], two[k]), k
+
+
 @pytest.mark.parametrize("name", sorted(synthetic.NEXT_SHAPES))
 def test_paper_10b_encoder_shards(name):
     _run(synthetic.NEXT_SHAPES[name])
