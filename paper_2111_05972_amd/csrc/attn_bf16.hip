@@ -32,6 +32,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <type_traits>
 
 #include "device_math.h"
 #include "kernels.h"
@@ -126,6 +127,37 @@ __device__ __forceinline__ bf16x8 frag_t(const char* tile, int d_base, int r_bas
     }
     return out;
 }
+// Byte offsets of those two kinds of read inside a tile, for kernels that keep them in registers across the streaming
+// loop (computed per read they are ~100 vector instructions per tile step, more than the softmax arithmetic itself;
+// matrix and vector instructions do not overlap on a SIMD, so every one of them is matrix time lost).  Both are
+// unchanged by adding a multiple of 16 to the row (the swizzle uses row bits 0..3 only): a second block of 16 rows is
+// the same offset plus 16 rows.
+template <int DH> __device__ __forceinline__ unsigned frag_k_off(int row_base, int ks, int lane) {
+    int row = row_base + (lane & 31);
+    int c = 2 * ks + (lane >> 5);
+    return (unsigned)(row * (DH * 2) + ((c ^ swz<DH>(row)) << 4));
+}
+template <int DH> __device__ __forceinline__ unsigned frag_t_off(int d_base, int r_base, int h, int lane) {
+    int l16 = lane & 15;
+    int d = d_base + (lane & 16) + 4 * (l16 & 3);
+    int row = r_base + 8 * h + 4 * (lane >> 5) + (l16 >> 2);
+    return (unsigned)(row * (DH * 2) + ((((d >> 3) ^ swz<DH>(row))) << 4) + (d & 7) * 2);
+}
+typedef __attribute__((address_space(3))) const bf16x8* lds_bf16x8_cptr;
+// The reads themselves from a 32-bit LDS address held in a register plus a compile-time byte offset (an immediate).
+template <int IMM> __device__ __forceinline__ bf16x8 lds_frag_k(unsigned addr) {
+    return *reinterpret_cast<lds_bf16x8_cptr>((uintptr_t)(addr + IMM));
+}
+template <int IMM> __device__ __forceinline__ bf16x8 lds_frag_t(unsigned addr0, unsigned addr1) {
+    s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(addr0 + IMM));
+    s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(uintptr_t)(addr1 + IMM));
+    bf16x4 b0 = __builtin_bit_cast(bf16x4, v0), b1 = __builtin_bit_cast(bf16x4, v1);
+    bf16x8 out;
+    out[0] = b0[0]; out[1] = b0[1]; out[2] = b0[2]; out[3] = b0[3];
+    out[4] = b1[0]; out[5] = b1[1]; out[6] = b1[2]; out[7] = b1[3];
+    return out;
+}
+template <typename T> __device__ __forceinline__ void keep_in_register(T& v) { asm volatile("" : "+v"(v)); }
 // The same operand straight from global memory (loop-invariant fragments kept in registers).
 template <int DH>
 __device__ __forceinline__ bf16x8 frag_k_global(const bf16_t* base, int64_t ld, int row, int nrows,
@@ -281,16 +313,25 @@ __global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(co
         tile_dma<DH, FTHREADS>(desc_k, stage, off, r0, wave_u);
         tile_dma<DH, FTHREADS>(desc_v, stage + TB, off, r0, wave_u);
     };
+    // LDS addresses of this lane's fragment reads in stage 0 (K tile at lds0, V tile one tile further), kept in registers
+    unsigned ka[DH / 16], va[DH / 32][2];
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) { ka[ks] = lds0 + frag_k_off<DH>(kvh * 32, ks, lane); keep_in_register(ka[ks]); }
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) { va[dt][h] = lds0 + TB + frag_t_off<DH>(dt * 32, kvh * 32, h, lane); keep_in_register(va[dt][h]); }
     fetch_tile(tile0, lds0);
 #pragma unroll
     for (int ks = 0; ks < DH / 16; ++ks) settle(qf[ks]);
     dma_wait();
     __syncthreads();
-    for (int kt = tile0; kt < ntiles; ++kt) {
-        const char* ks_ = smem + ((kt - tile0) & 1) * 2 * TB;
-        const char* vs_ = ks_ + TB;
+    // one tile step on ring stage STG (a compile-time constant, so that the stage is an immediate of every fragment read)
+    auto step = [&](int kt, auto stg) __attribute__((always_inline)) {
+        constexpr int STG = decltype(stg)::value;
+        constexpr int SOFF = STG * 2 * TB;
         // the other stage was last read before the barrier that ended the previous step
-        if (kt + 1 < ntiles) fetch_tile(kt + 1, lds0 + ((kt - tile0 + 1) & 1) * 2 * TB);
+        if (kt + 1 < ntiles) fetch_tile(kt + 1, lds0 + (1 - STG) * 2 * TB);
         const int kv0 = kt * TILE + kvh * 32;
         if (kv0 < kv_end && !(CAUSAL && kv0 > q0 + 31)) {                 // wavefront-uniform
             // All K fragments are requested before the first MFMA and all V fragments before the softmax arithmetic,
@@ -298,7 +339,7 @@ __global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(co
             f32x16 s = zero16();
             bf16x8 fr[DH / 16];
 #pragma unroll
-            for (int ks = 0; ks < DH / 16; ++ks) fr[ks] = frag_k<DH>(ks_, kvh * 32, ks, lane);
+            for (int ks = 0; ks < DH / 16; ++ks) fr[ks] = lds_frag_k<SOFF>(ka[ks]);
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_setprio(1);
 #pragma unroll
@@ -307,8 +348,8 @@ __global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(co
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int dt = 0; dt < DH / 32; ++dt) {
-                fr[2 * dt] = frag_t<DH>(vs_, dt * 32, kvh * 32, lane);
-                fr[2 * dt + 1] = frag_t<DH>(vs_, dt * 32, kvh * 32 + 16, lane);
+                fr[2 * dt] = lds_frag_t<SOFF>(va[dt][0], va[dt][1]);
+                fr[2 * dt + 1] = lds_frag_t<SOFF + 16 * DH * 2>(va[dt][0], va[dt][1]);
             }
             __builtin_amdgcn_sched_barrier(0);
             // masking is needed only in tiles that straddle the diagonal or the end of the sequence
@@ -353,6 +394,14 @@ __global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(co
         }
         dma_wait();
         __syncthreads();
+    };
+    {
+        int kt = tile0;
+        for (; kt + 1 < ntiles; kt += 2) {
+            step(kt, std::integral_constant<int, 0>{});
+            step(kt + 1, std::integral_constant<int, 1>{});
+        }
+        if (kt < ntiles) step(kt, std::integral_constant<int, 0>{});
     }
     lsum += __shfl_xor(lsum, 32, 64);
     // merge the two key halves: wavefronts 4..7 hand (m, l, O) to wavefronts 0..3 through LDS
