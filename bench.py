@@ -431,6 +431,44 @@ def bench_layer(args, cfg, dt, pkg, torch, synthetic, ckpt=False, extras=True, o
     return out
 
 
+def bench_attention(args, cfg, dt, pkg, torch, synthetic):
+    """The attention kernels of the config alone (tp_layer_attn_fwd, tp_layer_attn_bwd on its [B, S, local heads, dh]),
+    random inputs, no workspace (strips whole, as inside the layer): time and rate of each."""
+    B, S, nl, dh, causal = cfg.micro_batch, cfg.seq, cfg.local_heads, cfg.head_dim, cfg.causal
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    st = torch.cuda.current_stream()
+    qkv = torch.randn(B * S, 3 * nl * dh, device="cuda", dtype=tdt)
+    o = torch.empty(B * S, nl * dh, device="cuda", dtype=tdt)
+    d_o = torch.randn_like(o)
+    lse = torch.empty(B, nl, S, device="cuda", dtype=torch.float32)
+    dsum = torch.empty_like(lse)
+    dqkv = torch.empty_like(qkv)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(args.steps):
+            fn()
+        e1.record(st)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+    fwd_ms = timed(lambda: pkg.tp_layer_attn_fwd(dt, B, S, nl, dh, causal, qkv, o, lse, stream=st))
+    bwd_ms = timed(lambda: pkg.tp_layer_attn_bwd(dt, B, S, nl, dh, causal, qkv, o, lse, d_o, dqkv, dsum, stream=st))
+    pairs = S * (S + 1) // 2 if causal else S * S
+    flops = 4.0 * B * nl * pairs * dh
+    peak = F32_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_PEAK_TFLOPS
+    tf = 3.0 * flops / ((fwd_ms + bwd_ms) * 1e-3) / 1e12
+    return {"metric": "TFLOP/s of the attention kernels alone (forward + backward)", "value": round(tf, 1), "unit": "TFLOP/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(fwd_ms + bwd_ms, 4),
+            "higher_is_better": True, "dtype": cfg.dtype, "data": "synthetic",
+            "config": {"workload": f"attention of config {cfg.cfg_id}: {cfg.name} (B={B}, S={S}, local heads={nl}, dh={dh}, causal={causal})"},
+            "fwd": {"ms": round(fwd_ms, 4), "tflops": round(flops / fwd_ms / 1e9, 1), "frac_of_peak": round(flops / fwd_ms / 1e9 / peak, 4)},
+            "bwd": {"ms": round(bwd_ms, 4), "tflops": round(2 * flops / bwd_ms / 1e9, 1), "frac_of_peak": round(2 * flops / bwd_ms / 1e9 / peak, 4)}}
+
+
 def bench_gemms(args, cfg, dt, pkg, torch, synthetic):
     """The 12 GEMMs of a step, each alone in a sustained loop on random operands: this library (tp_layer_gemm) and,
     as a reference point of what the chip sustains on the same shape, the vendor library behind torch.matmul.  Two
@@ -539,12 +577,12 @@ def main():
                     help="skip the extra timing of the same shard with the row-parallel epilogue on")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="only the headline workload: skip the `other_workloads` block of the default run")
-    ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "ln", "memopt", "gemms"],
+    ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "ln", "memopt", "gemms", "attn"],
                     help="layer: tp_layer_fwd + tp_layer_bwd (the headline metric); layer-checkpoint: tp_layer_fwd + "
                          "tp_layer_bwd_recompute; ln: replicated LayerNorm forward + backward on the config's [M, H]; "
                          "memopt: one rank's local compute in the memory-optimised distribution at the config's widths; "
                          "gemms: each GEMM of a step alone in a sustained loop, beside the vendor library on the same shape, "
-                         "with board power and clock")
+                         "with board power and clock; attn: the attention kernels of the config alone")
     ap.add_argument("--single-stream", action="store_true",
                     help="time the plain schedule, every kernel on the caller's stream, instead of the two-chain "
                          "schedule (TPL_SIDE_STREAM: the MLP block of a pass on a second, library-owned stream)")
@@ -581,6 +619,9 @@ def main():
         return
     if args.workload == "gemms":
         print(json.dumps(bench_gemms(args, cfg, dt, pkg, torch, synthetic)))
+        return
+    if args.workload == "attn":
+        print(json.dumps(bench_attention(args, cfg, dt, pkg, torch, synthetic)))
         return
     out = bench_layer(args, cfg, dt, pkg, torch, synthetic, ckpt=args.workload == "layer-checkpoint")
 
