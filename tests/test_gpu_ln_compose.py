@@ -6,7 +6,8 @@ One composition function drives two backends in the same order: the HIP path (tp
 tp_layer_bwd / tp_layer_ln_bwd, all T ranks on the one GPU) and the oracle (float64, nothing rounded).  What the
 tensor-parallel group would all-reduce is summed over the ranks by the test (float sum, one rounding to the
 storage type on the GPU side).  Because the boundary takes the MLP block's input from the caller, a pass over a
-layer calls the shard twice (attention block first, then again once x_mlp is known), as the design doc explains.
+layer calls the shard twice (attention block first, then again once x_mlp is known; the second call recomputes the
+attention block, whose outputs are simply not used again).
 
 post-LN (the paper's default): x_a = h;           Ya = sum_r y_a;  x_m = LN1(Ya);      Ym = sum_r y_m;  out = LN2(Ym)
                                (rank 0 adds b_o + x_a and b_dn + x_m: TPL_ROW_EPILOGUE)
