@@ -431,6 +431,72 @@ def bench_layer(args, cfg, dt, pkg, torch, synthetic, ckpt=False, extras=True, o
     return out
 
 
+def bench_layer_ln(args, cfg, dt, pkg, torch, synthetic):
+    """One rank's kernels for a whole post-LN layer pass (Sec. I.1 / I.4): the shard forward, LN1 on the attention
+    block's sum and LN2 on the MLP block's sum; backward through LN2, the shard and LN1.  The all-reduces are not run
+    (one GPU): where the group's sum is needed the rank's own partial stands in, and the MLP block's input is the LN1
+    output of the previous pass, so every pass runs exactly the kernels a rank runs per layer.  Values are checked by
+    tests/test_gpu_ln_compose.py (all ranks on one GPU, against the oracle); this is timing only."""
+    M, H = cfg.tokens, cfg.hidden
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    d = synthetic.make_inputs(cfg)
+    host_sh = pkg.shard_params(d, cfg.tp_degree if cfg.global_params else 1, cfg.tp_rank if cfg.global_params else 0)
+    layer = pkg.TpLayer(cfg.hidden, cfg.heads, cfg.tp_degree, cfg.tp_rank, cfg.seq, cfg.micro_batch, dt, cfg.causal,
+                        cfg.row_epilogue, cfg.head_dim, cfg.intermediate, side_stream=not args.single_stream)
+    p = {k: pkg.to_device(v, dt) for k, v in host_sh.items()}
+    x = {k: pkg.to_device(d[k], dt) for k in ("x_a", "x_m", "dy_a", "dy_m")}
+    st = torch.cuda.current_stream()
+    y_a, y_m = layer.empty_outputs()
+    dx_a, dx_m = layer.empty_outputs()
+    grads = layer.empty_grads()
+    gam = [torch.ones(H, dtype=tdt, device="cuda") for _ in range(2)]
+    bet = [torch.zeros(H, dtype=tdt, device="cuda") for _ in range(2)]
+    x_m, out, d_ya, d_ym = (torch.empty(M, H, dtype=tdt, device="cuda") for _ in range(4))
+    x_m.copy_(x["x_m"]); d_ya.copy_(x["dy_a"])
+    mean = [torch.empty(M, dtype=torch.float32, device="cuda") for _ in range(2)]
+    rstd = [torch.empty(M, dtype=torch.float32, device="cuda") for _ in range(2)]
+    dg, db = torch.empty_like(gam[0]), torch.empty_like(gam[0])
+    ws = torch.empty(pkg.tp_layer_ln_workspace_bytes(M, H), dtype=torch.uint8, device="cuda")
+
+    def fwd():
+        layer.forward(p, x["x_a"], x_m, y_a, y_m, stream=st)
+        pkg.tp_layer_ln_fwd(dt, M, H, y_a, None, gam[0], bet[0], 1e-5, None, x_m, mean[0], rstd[0], stream=st)
+        pkg.tp_layer_ln_fwd(dt, M, H, y_m, None, gam[1], bet[1], 1e-5, None, out, mean[1], rstd[1], stream=st)
+
+    def bwd():
+        pkg.tp_layer_ln_bwd(dt, M, H, x["dy_m"], y_m, mean[1], rstd[1], gam[1], d_ym, dg, db, ws, stream=st)
+        layer.backward(p, x["x_a"], x_m, d_ya, d_ym, grads, dx_a, dx_m, stream=st)
+        pkg.tp_layer_ln_bwd(dt, M, H, dx_m, y_a, mean[0], rstd[0], gam[0], d_ya, dg, db, ws, stream=st)
+
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(n):
+            fn()
+        e1.record(st)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / n
+    for _ in range(args.warmup):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        fwd(); bwd()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t1) / args.steps
+    fwd_ms = timed(fwd, max(3, min(args.steps, 10)))
+    f_fwd, f_bwd = cfg.flops()
+    peak = F32_PEAK_TFLOPS if cfg.dtype == "f32" else BF16_PEAK_TFLOPS
+    tf = (f_fwd + f_bwd) / (ms * 1e-3) / 1e12
+    assert torch.isfinite(out.float()).all() and torch.isfinite(d_ya.float()).all()
+    return {"metric": "TFLOP/s (fwd+bwd) of one rank's kernels for a post-LN layer: shard + both LayerNorms; % of peak",
+            "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": cfg.dtype, "data": "synthetic", "pct_of_peak": round(100.0 * tf / peak, 2),
+            "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(ms - fwd_ms, 4),
+            "config": {"workload": f"config {cfg.cfg_id}: {cfg.name} with its two LayerNorms (post-LN layer, one rank's kernels)"}}
+
+
 def bench_attention(args, cfg, dt, pkg, torch, synthetic):
     """The attention kernels of the config alone (tp_layer_attn_fwd, tp_layer_attn_bwd on its [B, S, local heads, dh]),
     random inputs, no workspace (strips whole, as inside the layer): time and rate of each."""
@@ -577,12 +643,13 @@ def main():
                     help="skip the extra timing of the same shard with the row-parallel epilogue on")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="only the headline workload: skip the `other_workloads` block of the default run")
-    ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "ln", "memopt", "gemms", "attn"],
+    ap.add_argument("--workload", default="layer", choices=["layer", "layer-checkpoint", "layer-ln", "ln", "memopt", "gemms", "attn"],
                     help="layer: tp_layer_fwd + tp_layer_bwd (the headline metric); layer-checkpoint: tp_layer_fwd + "
                          "tp_layer_bwd_recompute; ln: replicated LayerNorm forward + backward on the config's [M, H]; "
                          "memopt: one rank's local compute in the memory-optimised distribution at the config's widths; "
                          "gemms: each GEMM of a step alone in a sustained loop, beside the vendor library on the same shape, "
-                         "with board power and clock; attn: the attention kernels of the config alone")
+                         "with board power and clock; attn: the attention kernels of the config alone; layer-ln: the shard with the "
+                         "two replicated LayerNorms of a post-LN layer around it, forward and backward")
     ap.add_argument("--single-stream", action="store_true",
                     help="time the plain schedule, every kernel on the caller's stream, instead of the two-chain "
                          "schedule (TPL_SIDE_STREAM: the MLP block of a pass on a second, library-owned stream)")
@@ -623,6 +690,9 @@ def main():
     if args.workload == "attn":
         print(json.dumps(bench_attention(args, cfg, dt, pkg, torch, synthetic)))
         return
+    if args.workload == "layer-ln":
+        print(json.dumps(bench_layer_ln(args, cfg, dt, pkg, torch, synthetic)))
+        return
     out = bench_layer(args, cfg, dt, pkg, torch, synthetic, ckpt=args.workload == "layer-checkpoint")
 
     # The default run also carries every other configuration and workload, each measured the same way (fewer steps;
@@ -650,6 +720,7 @@ def main():
         attempt("layer-checkpoint", lambda: bench_layer(oa, cfg, dt, pkg, torch, synthetic, ckpt=True, extras=False,
                                                         oracle_limit=0.0))
         attempt("ln", lambda: bench_layernorm(oa, cfg, dt, pkg, torch, synthetic))
+        attempt("layer-ln", lambda: bench_layer_ln(oa, cfg, dt, pkg, torch, synthetic))
         ma = copy.copy(oa)
         ma.no_cpu_baseline = args.no_cpu_baseline or time.time() - t_start > 200
         attempt("memopt", lambda: bench_memopt(ma, cfg, dt, pkg, torch, synthetic))
