@@ -118,6 +118,13 @@ def test_bias_gradients_inside_the_weight_gradient_gemm(fuse, tune):
         assert np.array_equal(a[k], b[k]), k
 
 
+def test_bias_gradients_inside_the_weight_gradient_gemm_at_full_size(tune):
+    """The same option at config 5 with the library's own plans (its weight gradients run on the kernel that can carry
+    the column sums): every tensor against the oracle."""
+    tune.set("fuse_colsum", "1")
+    _run(C[5])
+
+
 def test_run_to_run_determinism():
     cfg = SMALL[3]
     d, sh = shard_inputs(cfg)
