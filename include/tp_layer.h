@@ -35,7 +35,9 @@
  * tp_layer_fwd / tp_layer_bwd / tp_layer_bwd_recompute enqueue the attention block and the MLP
  * block, which share no tensor, as two chains, the second on a stream the library creates once per
  * device (default priority) and forks from / joins to `hip_stream` with events (also when the call
- * fails half-way).  That second stream and its events are shared by all calls on a device: host
+ * fails half-way); for small layers the backward pass runs a third chain (the two weight gradients
+ * that depend on nothing computed in the pass) on another such stream.  These streams and their
+ * events are shared by all calls on a device: host
  * threads that make such calls on the same device at the same time must serialise them.
  * Pointers must be 16-byte aligned.  Outputs must not alias inputs.  Gradients are overwritten,
  * not accumulated.  `ws` contents need not be preserved between calls; calls that share a `ws`
@@ -291,6 +293,8 @@ int tp_layer_profile_read(float* ms_out, int capacity, int* count);
  *   "gemm_band"   force the band height of the GEMM tile order
  *   "gemm_force"  "MxNxK@ab=v[:shares];..." plans for single shapes (a, b = 1 where A, B has K contiguous)
  *   "attn_chunk"  chunk length of attention strips in 64-row tile steps (0: never cut)
+ *   "side_chains" 2 or 3: chains of a backward pass under TPL_SIDE_STREAM (3: the two weight gradients that depend on
+ *                 nothing computed in the pass, dW_dn and dW_o, on a second library stream); unset: chosen by size
  *   "fuse_colsum" 1: the bias gradients db_qkv, db_up are one more output row of the weight-gradient GEMM whenever
  *                 its kernel supports that; 0 (default): they come from the column-sum kernels (measured inside the
  *                 whole step the two are equal on one stream and the fused form is 0.4 % slower on two chains)

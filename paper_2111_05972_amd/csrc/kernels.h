@@ -17,12 +17,14 @@ struct Options {
     int gemm_shares = 0;       // force a K split; 0: the planner chooses
     int gemm_band = 0;         // force the band height of the tile order; 0: choose_band
     int attn_chunk = -1;       // force the chunk length of attention strips in 64-row tile steps (0: never cut); -1: unset
+    int side_chains = 0;       // chains of a backward pass under TPL_SIDE_STREAM: 2, or 3 (dW_dn and dW_o on a stream of their
+                               // own); 0: the library chooses by the size of the weight gradients
     int fuse_colsum = 0;       // 1: bias gradients as one more output row of the weight-gradient GEMM where its kernel can
     char gemm_force[1024] = "";   // "MxNxK@ab=v[:shares];..." plans of single shapes (a, b = 1: A, B K-major)
     unsigned generation = 0;
 };
 const Options& options();
-// name: "gemm_tile", "gemm_shares", "gemm_band", "gemm_force", "attn_chunk", "fuse_colsum"; value null or "": back to unset.
+// name: "gemm_tile", "gemm_shares", "gemm_band", "gemm_force", "attn_chunk", "fuse_colsum", "side_chains"; value null or "": back to unset.
 // Returns false for an unknown name or a value that does not parse.
 bool set_option(const char* name, const char* value);
 enum Epi { EPI_NONE = 0, EPI_GELU = 1, EPI_DGELU = 2 };

@@ -44,6 +44,7 @@ bool set_option(const char* name, const char* value) {
     else if (!strcmp(name, "gemm_band")) ok = parse_int(value, 0, 0, 1 << 20, &o.gemm_band);
     else if (!strcmp(name, "attn_chunk")) ok = parse_int(value, -1, 0, 1 << 16, &o.attn_chunk);
     else if (!strcmp(name, "fuse_colsum")) ok = parse_int(value, 0, 0, 1, &o.fuse_colsum);
+    else if (!strcmp(name, "side_chains")) ok = parse_int(value, 0, 2, 3, &o.side_chains);
     else if (!strcmp(name, "gemm_force")) {
         const char* v = value ? value : "";
         if (strlen(v) < sizeof(o.gemm_force)) { strcpy(o.gemm_force, v); ok = true; }
@@ -110,7 +111,7 @@ size_t gemm_ws(int dtype, int64_t M, int64_t N, int64_t K) {
 }
 
 // Backward scratch: dU, dO, dQKV, D, and per chain (attention, MLP) column-sum partials and GEMM scratch.
-struct BwdWs { size_t du, d_o, dqkv, dsum, colsum, colsum2, gemm, gemm2, gemm_each, attn, attn_bytes, total; };
+struct BwdWs { size_t du, d_o, dqkv, dsum, colsum, colsum2, gemm, gemm2, gemm3, gemm_each, attn, attn_bytes, total; };
 
 // Float partials of attention strips cut into chunks: inside a layer pass only when TPL_ATTN_CHUNK forces a chunk
 // length (own_chunking stays 0: see attn_bf16.hip), so normally 0.
@@ -150,6 +151,7 @@ void bwd_layout(const Dims& x, BwdWs* W) {
     W->gemm_each = g;
     W->gemm = off; off += g;
     W->gemm2 = off; off += g;
+    W->gemm3 = off; off += g;      // the two weight gradients that depend on nothing computed in the pass (third chain)
     W->attn_bytes = attn_ws(x, true);
     W->attn = off; off += W->attn_bytes;
     W->total = off;
@@ -180,15 +182,16 @@ struct SideStream {
     int state = 0;       // 0 = not tried, 1 = ready, -1 = unavailable
 };
 constexpr int MAX_DEVICES = 64;
-SideStream g_side[MAX_DEVICES];
+constexpr int MAX_SIDE = 2;
+SideStream g_side[MAX_DEVICES][MAX_SIDE];
 
 // Returns the stream for the second chain, already waiting for everything enqueued on s so far; s itself when
 // the second stream is not used.
-hipStream_t side_fork(hipStream_t s, bool wanted) {
+hipStream_t side_fork(hipStream_t s, bool wanted, int which = 0) {
     if (!wanted || g_prof.on) return s;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return s;
-    SideStream& ss = g_side[dev];
+    SideStream& ss = g_side[dev][which];
     if (ss.state == 0) {
         ss.state = (hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
                     hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
@@ -199,11 +202,11 @@ hipStream_t side_fork(hipStream_t s, bool wanted) {
     return ss.stream;
 }
 // Makes s wait for everything enqueued on the second stream.
-int side_join(hipStream_t s, hipStream_t s2) {
+int side_join(hipStream_t s, hipStream_t s2, int which = 0) {
     if (s2 == s) return TPL_OK;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return TPL_EHIP;
-    SideStream& ss = g_side[dev];
+    SideStream& ss = g_side[dev][which];
     if (hipEventRecord(ss.join, s2) != hipSuccess || hipStreamWaitEvent(s, ss.join, 0) != hipSuccess) return TPL_EHIP;
     return TPL_OK;
 }
@@ -211,9 +214,10 @@ int side_join(hipStream_t s, hipStream_t s2) {
 // on the second stream that touches the caller's buffers.
 struct SideJoin {
     hipStream_t s, s2;
+    int which = 0;
     bool done = false;
-    int finish() { done = true; return side_join(s, s2); }
-    ~SideJoin() { if (!done) side_join(s, s2); }
+    int finish() { done = true; return side_join(s, s2, which); }
+    ~SideJoin() { if (!done) side_join(s, s2, which); }
 };
 
 int run_gemm(GemmArgs& g) {
@@ -340,13 +344,23 @@ int bwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
     float *dsum = (float*)(w + W.dsum), *cs = (float*)(w + W.colsum), *cs2 = (float*)(w + W.colsum2);
     hipStream_t s2 = side_fork(s, x.side_stream);
     SideJoin sj{s, s2};
+    // dW_dn and dW_o need only the pass's inputs and saved activations: they can form a third chain on a stream of
+    // their own (option side_chains = 2 or 3 forces the number of chains)
+    // (measured inside whole steps: -4 % at the RoBERTa-large shard and -2 % at the BERT-large one, whose GEMMs leave
+    // compute units idle; +1 to +2 % at the 10B and GPT-3 shards, whose GEMMs fill the chip and only get in each other's
+    // way; left to itself the library takes three chains below 45 GFLOP per weight gradient)
+    const int chains = options().side_chains ? options().side_chains
+                                             : (2.0 * (double)x.Il * (double)x.H * (double)x.M < 45.0e9 ? 3 : 2);
+    hipStream_t s3 = chains >= 3 ? side_fork(s, x.side_stream, 1) : nullptr;
+    SideJoin sj3{s, s3 ? s3 : s, 1};
     GemmScratch sc{w + W.gemm, W.gemm_each, s}, sc2{w + W.gemm2, W.gemm_each, s2};
+    GemmScratch sc3a{w + W.gemm3, W.gemm_each, s3 ? s3 : s2}, sc3b{w + W.gemm3, W.gemm_each, s3 ? s3 : s};
 
     // MLP block (second chain).  dU = (dy_m W_dn^T) * gelu'(U) in one GEMM epilogue.
     GemmArgs b5 = mk(x, 0, 1, x.M, x.Il, x.H, dy_mlp, p->w_dn, du, sc2);
     b5.aux = const_cast<void*>(u); b5.epi = EPI_DGELU;
     if ((rc = run_gemm(b5))) return rc;
-    GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, sc2);
+    GemmArgs w5 = mk(x, 1, 0, x.Il, x.H, x.M, g, dy_mlp, gr->dw_dn, s3 ? sc3a : sc2);
     w5.c_streaming = true;                   // the weight gradient is not read again in this pass
     if ((rc = run_gemm(w5))) return rc;
     GemmArgs w4 = mk(x, 1, 0, x.H, x.Il, x.M, x_mlp, du, gr->dw_up, sc2);
@@ -362,7 +376,7 @@ int bwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
     // attention block
     GemmArgs d3 = mk(x, 0, 1, x.M, x.Hl, x.H, dy_attn, p->w_o, d_o, sc);
     if ((rc = run_gemm(d3))) return rc;
-    GemmArgs w3 = mk(x, 1, 0, x.Hl, x.H, x.M, o, dy_attn, gr->dw_o, sc);
+    GemmArgs w3 = mk(x, 1, 0, x.Hl, x.H, x.M, o, dy_attn, gr->dw_o, s3 ? sc3b : sc);
     w3.c_streaming = true;
     if ((rc = run_gemm(w3))) return rc;
     if (x.row_epi && colsum(x.dtype, x.M, x.H, dy_attn, gr->db_o, cs, s) != hipSuccess) return TPL_EHIP;
@@ -381,6 +395,7 @@ int bwd_impl(const Dims& x, const tp_layer_params* p, const void* x_attn, const 
     GemmArgs d1 = mk(x, 0, 1, x.M, x.H, 3 * x.Hl, dqkv, p->w_qkv, dx_attn, sc);
     if (x.row_epi) d1.resid = dy_attn;
     if ((rc = run_gemm(d1))) return rc;
+    if ((rc = sj3.finish())) { return rc; }
     return sj.finish();
 }
 }  // namespace

@@ -32,7 +32,7 @@ def pytest_collection_modifyitems(config, items):
 
 class _Tune:
     """Sets the library's tuning overrides (tp_layer_set_option) for one test; all are cleared afterwards."""
-    NAMES = ("gemm_tile", "gemm_shares", "gemm_band", "gemm_force", "attn_chunk", "fuse_colsum")
+    NAMES = ("gemm_tile", "gemm_shares", "gemm_band", "gemm_force", "attn_chunk", "fuse_colsum", "side_chains")
 
     def set(self, name, value):
         import paper_2111_05972_amd as pkg

@@ -76,6 +76,19 @@ def test_two_chain_schedule_at_full_size(cid):
         assert np.array_equal(one[k], two[k]), k
 
 
+def test_three_chain_backward(tune):
+    """Option side_chains = 3: dW_dn and dW_o, which depend on nothing computed in the pass, on a stream of their own.
+    Against the oracle and bit-identical to the one-stream schedule."""
+    tune.set("side_chains", "3")
+    cfg = C[3]
+    d, sh = shard_inputs(cfg)
+    three = gpu_outputs(cfg, d, sh, side_stream=True)
+    compare(cfg, three, oracle_outputs(cfg, d, sh))
+    one = gpu_outputs(cfg, d, sh)
+    for k in one:
+        assert np.array_equal(one[k], three[k]), k
+
+
 @pytest.mark.parametrize("name", sorted(synthetic.NEXT_SHAPES))
 def test_paper_10b_encoder_shards(name):
     _run(synthetic.NEXT_SHAPES[name])
