@@ -185,6 +185,13 @@ __device__ __forceinline__ void store4(bf16_t* p, float a, float b, float c, flo
     o[0] = (bf16_t)a; o[1] = (bf16_t)b; o[2] = (bf16_t)c; o[3] = (bf16_t)d;
     *reinterpret_cast<bf16x4*>(p) = o;
 }
+// max(v[l], v[l ^ 32]) in every lane by one lane-swap instruction (no trip through the LDS crossbar, whose latency would
+// sit in the middle of the softmax chain): swapping the upper half of a with the lower half of b, for a = b = v, leaves
+// (v.lo, v.lo) and (v.hi, v.hi).
+__device__ __forceinline__ float cross_half_max(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 // 2^x on the hardware transcendental unit (arguments here are <= ~0; results below 2^-126 flush to 0).
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
@@ -364,7 +371,7 @@ __global__ __launch_bounds__(FTHREADS, DH == 64 ? 4 : 2) void attn_fwd_kernel(co
             float mb = s[0];
 #pragma unroll
             for (int v = 1; v < 16; ++v) mb = fmaxf(mb, s[v]);
-            mb = fmaxf(mb, __shfl_xor(mb, 32, 64)) * c2;      // c2 > 0: scaling commutes with max
+            mb = cross_half_max(mb) * c2;                     // c2 > 0: scaling commutes with max
             // The reference point m of the running sums moves only when the maximum has grown by more than
             // RESCALE_LAG (log2 units): probabilities then reach 2^RESCALE_LAG at most, which float sums and
             // bf16 operands hold without loss, and the accumulators are rescaled in a few early tiles only
